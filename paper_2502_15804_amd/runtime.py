@@ -1,0 +1,59 @@
+"""Device-side plumbing around the C ABI: keeps one layer's tensors and plan resident.
+
+Nothing here computes: it allocates torch tensors, copies the host plan to the device
+once, and forwards to fairkv_decode_attn.  Budgets are static after compression (the
+paper's scheme is a static, load-aware one: Section 4.1), so a layer is planned once
+and the plan is reused for every decode step.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import (FAIRKV_POLICY_LPT_SPLIT, Plan, fairkv_decode_attn, fairkv_default_params, fairkv_plan,
+               fairkv_workspace_bytes)
+
+
+def device_compute_units(device=None) -> int:
+    import torch
+    return int(torch.cuda.get_device_properties(device if device is not None else torch.cuda.current_device())
+               .multi_processor_count)
+
+
+class DecodeLayer:
+    """One layer's packed ragged KV cache, its plan and its output buffers on the GPU."""
+
+    def __init__(self, q, k, v, off, lens, scale, params=None, out_dtype=None, want_lse=True,
+                 workspace=None):
+        import torch
+
+        dev = q.device
+        self.q, self.k, self.v = q, k, v
+        self.B, self.Hq, self.D = q.shape
+        lens_h = np.ascontiguousarray(np.asarray(lens, dtype=np.int32))
+        off_h = np.ascontiguousarray(np.asarray(off, dtype=np.int64))
+        self.Hkv = lens_h.shape[1]
+        self.G = self.Hq // self.Hkv
+        self.scale = float(scale)
+        if params is None:
+            params = fairkv_default_params(device_compute_units(dev), policy=FAIRKV_POLICY_LPT_SPLIT)
+        self.plan: Plan = fairkv_plan(lens_h, self.B, self.Hkv, params)
+        self.lens_d = torch.from_numpy(lens_h).to(dev)
+        self.off_d = torch.from_numpy(off_h).to(dev)
+        items_bytes = self.plan.items.view(np.uint8) if self.plan.n_items else np.zeros(32, np.uint8)
+        self.items_d = torch.from_numpy(items_bytes.copy()).to(dev)
+        if not self.plan.n_items:
+            self.items_d = self.items_d[:0]
+        self.part_base_d = torch.from_numpy(self.plan.part_base).to(dev)
+        need = fairkv_workspace_bytes(self.plan.n_parts, self.G, self.D)
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        elif workspace.numel() < need:
+            raise ValueError("shared workspace too small for this layer")
+        self.workspace = workspace
+        self.out = torch.empty((self.B, self.Hq, self.D), dtype=out_dtype or torch.float32, device=dev)
+        self.lse = torch.empty((self.B, self.Hq), dtype=torch.float32, device=dev) if want_lse else None
+
+    def run(self, stream=None):
+        fairkv_decode_attn(self.q, self.k, self.v, self.off_d, self.lens_d, self.items_d, self.part_base_d,
+                           self.plan.n_parts, self.workspace, self.out, self.lse, self.scale, stream)
+        return self.out, self.lse

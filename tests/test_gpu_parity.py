@@ -1,0 +1,179 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
+seeded inputs, element by element.  Bars: max-abs-error 1e-5 (fp32 inputs), 1e-2 (bf16
+inputs); log-sum-exp to the same bars."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import attention as OA
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _F():
+    import paper_2502_15804_amd as F
+    return F
+
+
+def make_case(B, Hq, Hkv, D, dtype, lens, seed, gap_rows=0):
+    w = W.Workload("case", B, Hq, Hkv, D, dtype, 1, 1e-5 if dtype == "f32" else 1e-2, "")
+    off, total = W.packed_offsets(lens, gap_rows=gap_rows)
+    q, k, v = W.make_qkv(w, total + 8, seed=seed)
+    return w, off, q, k, v
+
+
+def run_hip(w, q, k, v, off, lens, policy=2, n_slots=512, out_dtype=None, poison=True, **params):
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    F = _F()
+    p = F.fairkv_default_params(256, policy=policy, n_slots=n_slots, **params)
+    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype)
+    if poison:
+        layer.out.fill_(float("nan"))
+        layer.lse.fill_(float("nan"))
+        layer.workspace.fill_(0xFF)
+    layer.run()
+    torch.cuda.synchronize()
+    return layer.out.float().cpu().numpy().astype(np.float64), layer.lse.cpu().numpy().astype(np.float64), layer
+
+
+def check(w, q, k, v, off, lens, tol=None, **kw):
+    tol = tol or w.tol
+    out, lse, layer = run_hip(w, q, k, v, off, lens, **kw)
+    ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+    assert np.isfinite(out).all()
+    err = np.abs(out - ro).max()
+    assert err <= tol, f"max abs err {err:.3e} > {tol}"
+    empty = np.isneginf(rl)
+    assert np.array_equal(np.isneginf(lse), empty)
+    if (~empty).any():
+        lerr = np.abs(lse[~empty] - rl[~empty]).max()
+        assert lerr <= tol, f"lse err {lerr:.3e}"
+    return err, layer
+
+
+def test_tiny_workload_fp32():
+    w = W.WORKLOADS["tiny"]
+    lens = W.lens("tiny", seed=0)
+    off, total = W.packed_offsets(lens)
+    q, k, v = W.make_qkv(w, total, seed=0)
+    for policy in (0, 1, 2):
+        check(w, q, k, v, off, lens, policy=policy)
+    # force splitting even of these short heads: chunks of 16 tokens
+    err, layer = check(w, q, k, v, off, lens, policy=2, tile=16, min_chunk=16, n_slots=64, oversub=1)
+    assert layer.plan.n_items > 8
+
+
+@pytest.mark.parametrize("dtype,D,G", [("bf16", 128, 8), ("bf16", 128, 4), ("bf16", 128, 2), ("bf16", 128, 1),
+                                       ("bf16", 64, 8), ("bf16", 64, 2), ("f32", 64, 2), ("f32", 64, 8),
+                                       ("f32", 128, 4), ("f32", 128, 1)])
+def test_shapes_with_ragged_tails_and_chunks(dtype, D, G):
+    rng = np.random.default_rng(D * 10 + G)
+    B, Hkv = 3, 2
+    lens = rng.integers(1, 900, size=(B, Hkv)).astype(np.int32)
+    lens[0, 0] = 1            # a single token
+    lens[1, 1] = 0            # an empty head
+    lens[2, 0] = 64 * 7       # whole tiles exactly
+    lens[2, 1] = 64 * 5 + 1   # one token into a new tile
+    w, off, q, k, v = make_case(B, Hkv * G, Hkv, D, dtype, lens, seed=G, gap_rows=3)
+    for policy in (0, 2):
+        check(w, q, k, v, off, lens, policy=policy, n_slots=16, oversub=2, min_chunk=128)
+
+
+def test_chunked_equals_unchunked_on_the_gpu():
+    # same inputs through one item per pair and through many chunks: both within the bar,
+    # and close to each other (the merge is exact in real arithmetic)
+    rng = np.random.default_rng(3)
+    lens = rng.integers(200, 3000, size=(2, 2)).astype(np.int32)
+    w, off, q, k, v = make_case(2, 16, 2, 128, "bf16", lens, seed=5)
+    o1, l1, _ = run_hip(w, q, k, v, off, lens, policy=0)
+    o2, l2, layer = run_hip(w, q, k, v, off, lens, policy=2, n_slots=64, min_chunk=64, oversub=1)
+    assert layer.plan.n_items > 16
+    assert np.abs(o1 - o2).max() < 1e-4 and np.abs(l1 - l2).max() < 1e-4
+
+
+def test_all_heads_empty():
+    lens = np.zeros((2, 2), np.int32)
+    w, off, q, k, v = make_case(2, 8, 2, 128, "bf16", lens, seed=1)
+    out, lse, layer = run_hip(w, q, k, v, off, lens)
+    assert layer.plan.n_items == 0 and (out == 0).all() and np.isneginf(lse).all()
+
+
+def test_length_one_returns_the_value_row_exactly():
+    lens = np.ones((2, 4), np.int32)
+    w, off, q, k, v = make_case(2, 8, 4, 64, "f32", lens, seed=2, gap_rows=1)
+    out, lse, _ = run_hip(w, q, k, v, off, lens)
+    vn = v.numpy().astype(np.float64)
+    for b in range(2):
+        for hq in range(8):
+            assert np.array_equal(out[b, hq], vn[off[b, hq // 2]])
+
+
+def test_large_scores_do_not_overflow():
+    lens = np.array([[300]], np.int32)
+    w, off, q, k, v = make_case(1, 8, 1, 128, "f32", lens, seed=3)
+    k = k * 8.0      # scores of order +-100
+    check(w, q, k, v, off, lens, tol=2e-5, policy=2, n_slots=4, min_chunk=64, oversub=1)
+
+
+def test_rows_outside_the_heads_are_never_read():
+    rng = np.random.default_rng(7)
+    lens = rng.integers(1, 300, size=(2, 2)).astype(np.int32)
+    w, off, q, k, v = make_case(2, 8, 2, 128, "bf16", lens, seed=4, gap_rows=2)
+    owned = np.zeros(k.shape[0], bool)
+    for b in range(2):
+        for h in range(2):
+            owned[off[b, h]: off[b, h] + lens[b, h]] = True
+    k2, v2 = k.clone(), v.clone()
+    k2[torch.from_numpy(~owned)] = float("inf")
+    v2[torch.from_numpy(~owned)] = float("nan")
+    o1, l1, _ = run_hip(w, q, k, v, off, lens, n_slots=8, min_chunk=64)
+    o2, l2, _ = run_hip(w, q, k2, v2, off, lens, n_slots=8, min_chunk=64)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_bf16_output_rounding():
+    lens = np.array([[500, 77]], np.int32)
+    w, off, q, k, v = make_case(1, 8, 2, 128, "bf16", lens, seed=6)
+    o32, _, _ = run_hip(w, q, k, v, off, lens, n_slots=4, min_chunk=64)
+    o16, _, _ = run_hip(w, q, k, v, off, lens, n_slots=4, min_chunk=64, out_dtype=torch.bfloat16)
+    want = torch.from_numpy(o32.astype(np.float32)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(o16.astype(np.float32), want)
+
+
+def test_runs_are_bit_reproducible():
+    lens = W.lens("llama70b", layer=1)[:4]
+    w, off, q, k, v = make_case(4, 64, 8, 128, "bf16", lens, seed=8)
+    o1, l1, _ = run_hip(w, q, k, v, off, lens)
+    o2, l2, _ = run_hip(w, q, k, v, off, lens)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+@pytest.mark.parametrize("name", ["llama70b", "mistral24b", "faircopy", "stress"])
+def test_full_size_workloads_every_output(name):
+    """Full sizes, the launch configuration the benchmark times (default parameters for the
+    device's compute-unit count), every output element against the oracle."""
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    w = W.WORKLOADS[name]
+    for layer_idx in (0, w.n_layers - 1):
+        lens = W.lens(name, seed=0, layer=layer_idx)
+        off, total = W.packed_offsets(lens)
+        q, k, v = W.make_qkv(w, total, seed=0, layer=layer_idx)
+        layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale)
+        layer.out.fill_(float("nan"))
+        layer.run()
+        torch.cuda.synchronize()
+        out = layer.out.cpu().numpy().astype(np.float64)
+        lse = layer.lse.cpu().numpy().astype(np.float64)
+        ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+        err = np.abs(out - ro).max()
+        assert err <= w.tol, f"{name} layer {layer_idx}: max abs err {err:.3e}"
+        fin = np.isfinite(rl)
+        assert np.array_equal(np.isneginf(lse), ~fin) and np.abs(lse[fin] - rl[fin]).max() <= w.tol
+        for policy in ((0,) if layer_idx == 0 else ()):
+            p = _F().fairkv_default_params(256, policy=policy)
+            naive = DecodeLayer(layer.q, layer.k, layer.v, off, lens, w.scale, params=p)
+            naive.run()
+            torch.cuda.synchronize()
+            assert np.abs(naive.out.cpu().numpy().astype(np.float64) - ro).max() <= w.tol
