@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark: ragged per-head decode attention on one MI355X.
+
+A step is one call of fairkv_decode_attn (the split-KV decode kernel plus the chunk merge)
+on one layer's packed ragged KV cache.  Steps rotate over distinct layer buffers whose
+total size is several times the GPU's 256 MB memory-side cache, so that the K/V rows of a
+step are streamed from HBM and not from a cache.  Plans are built once per layer before
+the timed region (budgets are static once the cache is compressed; the paper's scheme is a
+static one, Section 4.1) and the planner's host time is reported separately.
+
+Prints ONE JSON line.  value = algorithmic bytes per second over the whole timed region:
+K and V rows of every retained token read once, q read once, out written once.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1280)
+    ap.add_argument("--warmup", type=int, default=128)
+    ap.add_argument("--workload", default="llama70b")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer buffers to rotate over (0 = workload default)")
+    ap.add_argument("--policy", type=int, default=2, help="0 naive, 1 LPT, 2 LPT with chunk split")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-extras", action="store_true", help="skip the policy comparison and the CPU baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--seed", type=int, default=0)
+    for name in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens"):
+        ap.add_argument("--" + name.replace("_", "-"), type=int, default=None)
+    return ap.parse_args()
+
+
+class Rotation:
+    """Distinct layer buffers of one workload, resident on the GPU, with their plans."""
+
+    def __init__(self, name, n_layers, seed, policy, overrides):
+        import torch
+        import workloads as W
+        import paper_2502_15804_amd as F
+        from paper_2502_15804_amd.runtime import DecodeLayer, device_compute_units
+
+        self.w = W.WORKLOADS[name]
+        self.n_cu = device_compute_units()
+        self.params = F.fairkv_default_params(self.n_cu, policy=policy, **overrides)
+        self.lens, self.offs, self.layers, self.bytes = [], [], [], []
+        plan_times = []
+        need = 0
+        for li in range(n_layers):
+            lens = W.lens(name, seed=seed, layer=li)
+            t0 = time.perf_counter()
+            plan = F.fairkv_plan(lens, self.w.B, self.w.Hkv, self.params)
+            plan_times.append(time.perf_counter() - t0)
+            need = max(need, F.fairkv_workspace_bytes(plan.n_parts, self.w.G, self.w.D))
+        self.workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
+        for li in range(n_layers):
+            lens = W.lens(name, seed=seed, layer=li)
+            off, total = W.packed_offsets(lens)
+            q, k, v = W.make_qkv(self.w, total, seed=seed, layer=li, device="cuda")
+            self.layers.append(DecodeLayer(q, k, v, off, lens, self.w.scale, params=self.params,
+                                           workspace=self.workspace))
+            self.lens.append(lens)
+            self.offs.append(off)
+            self.bytes.append(W.algorithmic_bytes(self.w, lens))
+        self.plan_us = 1e6 * sorted(plan_times)[len(plan_times) // 2]
+        torch.cuda.synchronize()
+
+    def run_eager(self, first, count):
+        n = len(self.layers)
+        for i in range(first, first + count):
+            self.layers[i % n].run()
+
+    def capture(self):
+        import torch
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            self.run_eager(0, len(self.layers))       # load code objects before capturing
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            self.run_eager(0, len(self.layers))
+        return g
+
+
+def timed(rot, steps, warmup, use_graph):
+    """Returns (seconds by host clock, seconds by HIP events, bytes moved) for exactly `steps` steps."""
+    import torch
+    n = len(rot.layers)
+    graph = rot.capture() if use_graph else None
+
+    def go(first, count):
+        full, rest = (count // n, count % n) if (graph is not None and first % n == 0) else (0, count)
+        for _ in range(full):
+            graph.replay()
+        rot.run_eager(first + full * n, rest)
+
+    go(0, warmup)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start = (warmup + n - 1) // n * n          # begin the timed steps on a rotation boundary
+    t0 = time.perf_counter()
+    e0.record()
+    go(start, steps)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    moved = sum(rot.bytes[(start + i) % n] for i in range(steps))
+    return t1 - t0, e0.elapsed_time(e1) * 1e-3, moved
+
+
+def cpu_baseline(rot, seconds):
+    """The fp64 oracle, as it stands, on the host cores: whole layers of the same workload."""
+    import workloads as W
+    from oracle import attention as OA
+
+    done_bytes, spent, n_done = 0, 0.0, 0
+    threads = OA.max_threads()
+    host = [tuple(W.to_numpy_bits(t) for t in (l.q, l.k, l.v)) for l in rot.layers[:8]]
+    while spent < seconds:
+        li = n_done % len(host)
+        q, k, v = host[li]
+        t0 = time.perf_counter()
+        OA.attention(q, k, v, rot.offs[li], rot.lens[li], rot.w.scale)
+        spent += time.perf_counter() - t0
+        done_bytes += rot.bytes[li]
+        n_done += 1
+    return {"value": round(done_bytes / spent / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n_done} whole-layer passes over {len(host)} layer(s) of {rot.w.name}, every output, {spent:.1f} s",
+            "ms_per_layer": round(1e3 * spent / n_done, 2)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as W
+    import paper_2502_15804_amd as F
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU", file=sys.stderr)
+        sys.exit(2)
+    F.lib()
+    w = W.WORKLOADS[a.workload]
+    n_layers = a.layers or w.n_layers
+    overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens")
+                 if getattr(a, k) is not None}
+    rot = Rotation(a.workload, n_layers, a.seed, a.policy, overrides)
+    host_s, ev_s, moved = timed(rot, a.steps, a.warmup, not a.no_graph)
+    gbs = moved / ev_s / 1e9
+    ms_step = 1e3 * ev_s / a.steps
+
+    plan0 = rot.layers[0].plan
+    loads_max, loads_min = int(plan0.summary.max_slot_load), int(plan0.summary.min_slot_load)
+    rec = {
+        "metric": "achieved HBM GB/s, ragged per-head GQA decode attention (algorithmic bytes / time)",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.description}", "storage": w.dtype, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv,
+                   "D": w.D, "layers_rotated": n_layers, "rotation_GB": round(sum(rot.bytes) / 1e9, 3),
+                   "policy": a.policy, "n_slots": int(rot.params.n_slots), "min_chunk": int(rot.params.min_chunk),
+                   "oversub": int(rot.params.oversub), "graph_replay": not a.no_graph,
+                   "items_layer0": plan0.n_items},
+        "us_per_layer": round(1e3 * ms_step, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "host_clock_GBs": round(moved / host_s / 1e9, 1),
+        "plan_host_us_per_layer": round(rot.plan_us, 1),
+        "plan_layer0": {"max_slot_load": loads_max, "min_slot_load": loads_min},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "fairkv_decode_kernel + fairkv_merge_kernel (one step)",
+                     "bytes_per_launch": round(moved / a.steps), "us_per_launch": round(1e3 * ms_step, 3)},
+        "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
+                         "(Llama-3.3-70B, Section 5.2.2); other hardware, not this metric",
+    }
+    if not a.no_extras:
+        short = max(n_layers * 4, 64)
+        for pol, key in ((0, "naive"), (1, "lpt_nosplit")):
+            if pol == a.policy:
+                continue
+            r2 = Rotation(a.workload, n_layers, a.seed, pol, overrides)
+            _, ev2, moved2 = timed(r2, short, n_layers, not a.no_graph)
+            rec[f"{key}_GBs"] = round(moved2 / ev2 / 1e9, 1)
+            rec[f"gain_vs_{key}"] = round(gbs / (moved2 / ev2 / 1e9), 3)
+            del r2
+            torch.cuda.empty_cache()
+        rec["cpu_baseline"] = cpu_baseline(rot, a.cpu_seconds)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfairkv.so")
-SOURCES = [os.path.join(CSRC, "fairkv_kernels.hip"), os.path.join(CSRC, "fairkv_plan.cpp")]
-HEADERS = [os.path.join(ROOT, "include", "fairkv.h")]
+SOURCES = [os.path.join(CSRC, "fairkv_api.hip"), os.path.join(CSRC, "fairkv_plan.cpp")]
+HEADERS = [os.path.join(ROOT, "include", "fairkv.h")] + [os.path.join(CSRC, h) for h in ("common.h", "decode_mfma.h", "decode_valu.h", "merge.h")]
 
 
 def is_stale() -> bool:
@@ -25,7 +25,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wextra", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
            "-I", os.path.join(ROOT, "include"), "-x", "hip", *SOURCES, "-o", LIB]
     if verbose:
         cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")

@@ -83,14 +83,17 @@ def test_shapes_with_ragged_tails_and_chunks(dtype, D, G):
 
 def test_chunked_equals_unchunked_on_the_gpu():
     # same inputs through one item per pair and through many chunks: both within the bar,
-    # and close to each other (the merge is exact in real arithmetic)
+    # and close to each other.  The merge is exact in real arithmetic; what differs is the
+    # rounding of the softmax weights to bf16 (relative 2^-9) against different running maxima.
     rng = np.random.default_rng(3)
     lens = rng.integers(200, 3000, size=(2, 2)).astype(np.int32)
     w, off, q, k, v = make_case(2, 16, 2, 128, "bf16", lens, seed=5)
     o1, l1, _ = run_hip(w, q, k, v, off, lens, policy=0)
     o2, l2, layer = run_hip(w, q, k, v, off, lens, policy=2, n_slots=64, min_chunk=64, oversub=1)
     assert layer.plan.n_items > 16
-    assert np.abs(o1 - o2).max() < 1e-4 and np.abs(l1 - l2).max() < 1e-4
+    assert np.abs(o1 - o2).max() < 2e-3 and np.abs(l1 - l2).max() < 2e-3
+    ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+    assert np.abs(o1 - ro).max() <= w.tol and np.abs(o2 - ro).max() <= w.tol
 
 
 def test_all_heads_empty():
@@ -168,6 +171,7 @@ def test_full_size_workloads_every_output(name):
         lse = layer.lse.cpu().numpy().astype(np.float64)
         ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
         err = np.abs(out - ro).max()
+        print(f"{name} layer {layer_idx}: items={layer.plan.n_items} max_abs_err={err:.3e}")
         assert err <= w.tol, f"{name} layer {layer_idx}: max abs err {err:.3e}"
         fin = np.isfinite(rl)
         assert np.array_equal(np.isneginf(lse), ~fin) and np.abs(lse[fin] - rl[fin]).max() <= w.tol
