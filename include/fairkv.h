@@ -11,14 +11,15 @@
  * heavy heads so that each replica carries W/copies of the load (Algorithm 2;
  * objective eq. 4, cap on copies eq. 3, coverage eq. 2, efficiency eq. 5).
  * This library applies the same rule inside one GPU: the "devices" are
- * workgroup slots on compute units, a heavy pair is cut into equal token
- * chunks, and the chunks are scheduled longest first.
+ * persistent workgroups, one per compute unit, and a heavy pair is shared by
+ * several of them, each taking a token chunk.
  *
  * Conventions for every entry point
  *   - returns FAIRKV_OK (0) or a negative fairkv_status; never throws, aborts or prints;
  *   - "host" pointers are ordinary process memory, "device" pointers are HIP device
  *     memory of the current device; the library never allocates or frees device memory
- *     and keeps no state between calls; all buffers are owned by the caller;
+ *     and keeps no state between calls (the only state, the arrival counters, lives in
+ *     the caller's workspace); all buffers are owned by the caller;
  *   - on error nothing is launched and no output buffer is written.
  *
  * Packed ragged KV layout.  K and V are two row-major buffers [n_rows][D] of the
@@ -49,27 +50,39 @@ typedef enum {
 
 enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1 };
 
-/* How the work list is built.
- *   NAIVE      one item per pair, dealt round-robin in (b, h) order: the analogue of the
+/* How the work list is built; the four mirror the paper's ablation (Section 5.2.1).
+ *   NAIVE      pairs dealt to slots round-robin in (b, h) order, unsplit: the analogue of the
  *              paper's static head allocation baseline (Figure 3 (1), Section 5.1 Baseline).
- *   LPT        load-aware order, no splitting: Best-effort Assignment only (Section 1.2).
- *   LPT_SPLIT  heavy pairs cut into equal chunks first: with Fair-Copying (Section 4.2). */
-enum { FAIRKV_POLICY_NAIVE = 0, FAIRKV_POLICY_LPT = 1, FAIRKV_POLICY_LPT_SPLIT = 2 };
+ *   LPT        load-aware placement of whole pairs, longest first onto the least loaded slot:
+ *              Best-effort Assignment only (Section 1.2, Technique I).
+ *   LPT_SPLIT  Fair-Copying as the paper states it (Section 4.2, Algorithm 2): a heavy pair
+ *              becomes r equal chunks, each carrying len/r (the W/copies rule), then LPT.
+ *   FAIR       Fair-Copying taken to its limit on one GPU, where a replica may take any share:
+ *              all pairs are laid end to end and the line is cut into n_slots pieces of equal
+ *              cost, so a pair is shared only by the slots whose boundary falls inside it.
+ *              Reaches the lower bound of eq. 4 up to min_chunk and the per-item overhead. */
+enum { FAIRKV_POLICY_NAIVE = 0, FAIRKV_POLICY_LPT = 1, FAIRKV_POLICY_LPT_SPLIT = 2, FAIRKV_POLICY_FAIR = 3 };
 
-/* One unit of work: tokens [tok_begin, tok_begin + tok_count) of pair (b, h), for all G
- * query heads of the group.  chunk / n_chunks number the pieces of the pair; part is the
- * index of this item's partial result in the workspace; slot is the planner's predicted
- * placement (used for the summary; the kernels take items in list order). */
+/* One unit of work: tokens [tok_begin, tok_begin + tok_count) of pair (b, h), i.e. rows
+ * row ... row + tok_count - 1 of K and V, for all G query heads of the group.  n_chunks is
+ * the number of items the pair was cut into and part the index of this item's partial
+ * result (part_base[pair] + chunk index).  A pair without tokens has one item with
+ * tok_count == 0, so that some slot writes its zero output. */
 typedef struct {
-    int32_t b, h, tok_begin, tok_count, chunk, n_chunks, slot, part;
-} fairkv_item;
+    int64_t row;        /* off[b][h] + tok_begin */
+    int32_t tok_count;
+    int32_t b, h;
+    int32_t tok_begin;
+    int32_t n_chunks;
+    int32_t part;
+} fairkv_item;          /* 32 bytes */
 
 typedef struct {
-    int32_t n_slots;         /* workgroup slots to balance over (compute units x resident groups) */
-    int32_t tile;            /* chunk sizes are multiples of this many tokens (>= 1) */
-    int32_t min_chunk;       /* no chunk target below this; positive multiple of tile */
-    int32_t max_split;       /* most chunks one pair may be cut into: eq. 3's cap (>= 1) */
-    int32_t oversub;         /* aim for about n_slots * oversub chunks in total (>= 1) */
+    int32_t n_slots;         /* persistent workgroup slots to balance over (one per compute unit) */
+    int32_t tile;            /* cuts inside a pair fall on multiples of this many tokens (>= 1) */
+    int32_t min_chunk;       /* no piece of a cut pair is smaller; positive multiple of tile */
+    int32_t max_split;       /* most items one pair may be cut into: eq. 3's cap (>= 1) */
+    int32_t oversub;         /* LPT_SPLIT aims for about n_slots * oversub chunks in total (>= 1) */
     int32_t overhead_tokens; /* fixed cost of an item in token units: the offset of the
                                 linear latency model of Section 3.2 (>= 0) */
     int32_t policy;          /* FAIRKV_POLICY_* */
@@ -81,41 +94,52 @@ typedef struct {
     int64_t max_slot_load;   /* largest and smallest predicted slot load, in token units, */
     int64_t min_slot_load;   /*   over ALL n_slots (an idle slot counts 0): eq. 4 / Algorithm 2 */
     int32_t n_items;         /* items the plan has (also when it did not fit items_cap) */
-    int32_t n_parts;         /* partial-result slots the workspace must hold */
+    int32_t n_parts;         /* partial-result slots the workspace must hold (== n_items) */
 } fairkv_plan_summary;
 
-/* Defaults: n_slots = 2 * n_compute_units, tile 64, min_chunk 256, max_split 128,
- * oversub 2, overhead_tokens 64, policy LPT_SPLIT.  n_compute_units must be >= 1. */
+/* Defaults: n_slots = n_compute_units, tile 16, min_chunk 64, max_split 256, oversub 2,
+ * overhead_tokens 32, policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
 /*
- * Host-side planner (integer arithmetic only; deterministic).
+ * Host-side planner (integer arithmetic only; deterministic).  An item costs
+ * tok_count + overhead_tokens; the load of a slot is the sum over its items (objective: eq. 4).
  *
- *   target  = max(min_chunk, roundup_tile(ceil(sum len / (n_slots * oversub))))   [LPT_SPLIT]
- *   per pair with len > 0:  r = min(max_split, ceil(len / target)),  cs = roundup_tile(ceil(len / r)),
- *                           chunks of cs tokens, the last one shorter            (W / copies, Algorithm 2)
- *   order   = tok_count descending, then b, h, chunk ascending; each item goes to the slot
- *             with the smallest load so far (lowest index on ties); an item costs
- *             tok_count + overhead_tokens                                         (objective eq. 4)
- *   NAIVE and LPT never split; NAIVE keeps (b, h) order and deals slots round-robin.
+ * FAIR       pairs in (b, h) order fill slot 0, 1, ...  A slot opened as number j gets the budget
+ *            ceil((tokens not yet placed + overhead * (pairs unfinished + slots unopened)) /
+ *            slots unopened).  With fit = the whole tiles that still fit the slot's room: a pair
+ *            (or its rest) that fits is placed whole; else it is cut at `fit` if both pieces are
+ *            >= min_chunk; else it is placed whole anyway if the excess is <= fit; else the slot
+ *            is closed and the next one opened.  After a cut the rest goes on in the next slot.
+ *            The last slot, and the max_split-th piece of a pair, take all that is left.
+ * LPT_SPLIT  target = max(min_chunk, roundup_tile(ceil(sum len / (n_slots * oversub)))); a pair is
+ *            cut into r = min(max_split, ceil(len / target)) shares of roundup_tile(ceil(len / r))
+ *            tokens, the last one shorter (W / copies, Algorithm 2); shares are sorted by
+ *            tok_count descending, then pair and chunk ascending, and each goes to the slot with
+ *            the smallest load so far (lowest index on ties).
+ * LPT        the same with whole pairs.  NAIVE: whole pairs, pair i to slot i mod n_slots.
  *
- * len        host [B*Hkv], every entry >= 0; pairs with len == 0 get no item.
- * items      host [items_cap], out, in execution order; may be NULL iff items_cap == 0.
- * slot_ptr   host [n_slots+1] or NULL, out: CSR pointer over items grouped by slot.
- * part_base  host [B*Hkv+1] or NULL, out: chunks before each pair; pair p owns partial slots
+ * len, off   host [B*Hkv]: tokens and first row of every pair; len >= 0, off >= 0 where len > 0.
+ * items      host [items_cap], out, grouped by slot, inside a slot in the order the slot runs
+ *            them; may be NULL iff items_cap == 0.
+ * slot_ptr   host [n_slots+1] or NULL, out: slot j runs items[slot_ptr[j] .. slot_ptr[j+1]).
+ * part_base  host [B*Hkv+1] or NULL, out: items before each pair; pair p owns partial slots
  *            part_base[p] ... part_base[p+1]-1, in chunk order.
  * summary    host, out, required; filled whenever the arguments are valid.
  *
  * Returns FAIRKV_ECAP (after filling summary, slot_ptr and part_base, writing no item)
  * when the plan has more items than items_cap: call once with items_cap = 0 to size.
  */
-int fairkv_plan(const int32_t *len, int32_t B, int32_t Hkv, const fairkv_plan_params *p,
+int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, int32_t Hkv, const fairkv_plan_params *p,
                 fairkv_item *items, int32_t items_cap, int32_t *slot_ptr, int32_t *part_base,
                 fairkv_plan_summary *summary);
 
-/* Bytes of device workspace fairkv_decode_attn needs for n_parts partial results
- * (fp32 unnormalised outputs and softmax statistics per query head).  0 on bad arguments. */
-size_t fairkv_workspace_bytes(int32_t n_parts, int32_t G, int32_t D);
+/* Bytes of device workspace fairkv_decode_attn needs: fp32 partial outputs and softmax
+ * statistics for n_parts items, plus one arrival counter per pair.  0 on bad arguments.
+ * Layout: partial outputs, then statistics, then the counters, each region rounded up to
+ * 256 bytes.  The workspace must be zero-filled once before its first use (the arrival
+ * counters start at zero); every completed call leaves the counters at zero again. */
+size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D);
 
 /*
  * Decode attention for one layer: for every sequence b and query head hq (KV head
@@ -123,18 +147,19 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t G, int32_t D);
  * len[b][h] retained rows of pair (b, h), and lse[b][hq] = log sum exp of the scaled
  * scores.  Pairs with len == 0 give out = 0 and lse = -inf.  Accumulation is fp32.
  *
- * Enqueues a split-KV kernel over the work list (one workgroup per item; K/V rows are
- * read once and shared by the G query heads of the group) and a log-sum-exp merge of
- * the chunks of each pair on hip_stream, and returns without synchronising.
+ * Enqueues ONE kernel on hip_stream and returns without synchronising: n_slots persistent
+ * workgroups, workgroup j streaming the K/V rows of its items from HBM exactly once (shared
+ * by the G query heads of the group).  An item that is a whole pair writes out directly; the
+ * items of a cut pair leave partial results in the workspace and the one that finishes last
+ * combines them (log-sum-exp merge), so no second launch is needed.
  *
  * q          device [B][Hq][D], element type in_dtype
  * k, v       device [n_rows][D], element type in_dtype, 16-byte aligned
- * off, len   device [B*Hkv] (int64 rows / int32 tokens), the layout above
- * items      device [n_items] and part_base device [B*Hkv+1]: a plan made by fairkv_plan
- *            from the same len (copied to the device by the caller).  Every item must
- *            satisfy tok_begin + tok_count <= len[b][h]; tokens past len are not read.
- * workspace  device, at least fairkv_workspace_bytes(n_parts, G, D) bytes, 16-byte aligned;
- *            n_parts = the plan's summary.n_parts
+ * items      device [n_items], slot_ptr device [n_slots+1], part_base device [B*Hkv+1]: a plan
+ *            made by fairkv_plan from this cache's len and off, copied to the device by the
+ *            caller.  The kernels read exactly the rows the items name.
+ * workspace  device, at least fairkv_workspace_bytes(n_parts, B*Hkv, G, D) bytes, 16-byte
+ *            aligned, zero-filled before its first use (see fairkv_workspace_bytes)
  * out        device [B][Hq][D], element type out_dtype (FAIRKV_F32, or FAIRKV_BF16 rounded
  *            to nearest even)
  * lse        device [B][Hq] float, or NULL
@@ -142,13 +167,11 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t G, int32_t D);
  * hip_stream a hipStream_t (NULL = the default stream)
  *
  * Supported: D in {64, 128}; in_dtype BF16 or F32; G = Hq/Hkv in {1, 2, 4, 8}.
- * n_items == 0 is valid (every pair empty).  Calls that share a workspace must be
- * ordered on one stream.
+ * Calls that share a workspace must be ordered on one stream.
  */
 int fairkv_decode_attn(const void *q, const void *k, const void *v,
-                       const int64_t *off, const int32_t *len,
-                       const fairkv_item *items, int32_t n_items, const int32_t *part_base,
-                       int32_t n_parts, void *workspace, size_t workspace_bytes,
+                       const fairkv_item *items, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                       const int32_t *part_base, int32_t n_parts, void *workspace, size_t workspace_bytes,
                        void *out, float *lse,
                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
                        int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream);

@@ -9,53 +9,62 @@ W_A), replication is capped (eq. 3), every head must be placed (eq. 2), and a
 scheme is judged by max-minus-min group weight (Algorithm 2) and by the
 efficiency E = mean load / max load (eq. 5).  Its own search (Algorithms 1 and
 2) is exhaustive and meant for a handful of heads and GPUs.  On one GPU the
-"devices" are workgroup slots on compute units and the "heads" are hundreds of
-(sequence, KV head) pairs, so the same objective is pursued greedily:
+"devices" are persistent workgroup slots (one per compute unit) and the "heads"
+are hundreds of (sequence, KV head) pairs, so the same objective is pursued
+without search.  Four policies, mirroring the paper's ablation (Section 5.2.1):
 
-  * Fair-Copying becomes an equal split of a heavy pair's tokens into r chunks
-    (each carries len/r, the W/copies rule), r capped by max_split (eq. 3);
-  * Best-effort Assignment becomes longest-processing-time-first list
-    scheduling of the chunks over n_slots.
+  NAIVE      pairs dealt to slots round-robin, unsplit: static head allocation.
+  LPT        load-aware placement of whole pairs, longest first onto the least
+             loaded slot: Best-effort Assignment, no replication.
+  LPT_SPLIT  Fair-Copying as the paper states it: a heavy pair becomes r equal
+             chunks (each carries len/r, the W/copies rule, r capped by
+             max_split), then chunks are placed like LPT.
+  FAIR       Fair-Copying taken to its limit on one GPU, where a "replica" may
+             take any share: pairs are laid end to end and the line is cut into
+             n_slots pieces of equal cost, so a pair is shared only by the slots
+             whose boundary falls inside it.  Reaches the lower bound of eq. 4
+             up to one tile and the per-item overhead.
 
-Several plans can be equally good in the paper's sense; the order and
-tie-breaks below are fixed only so that two implementations can be compared
-field by field.  All arithmetic is on Python ints.
+An item costs tok_count + overhead_tokens (the linear latency model with an
+offset of Section 3.2).  Pairs with no tokens still get one empty item, so that
+some slot writes their zero output.  Several plans can be equally good in the
+paper's sense; order and tie-breaks are fixed only so that two implementations
+can be compared field by field.  All arithmetic is on Python ints.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass
 from typing import List, Tuple
 
-POLICY_NAIVE = 0      # one work item per pair, dealt round-robin (static head allocation)
-POLICY_LPT = 1        # load-aware assignment, no splitting (Best-effort Assignment only)
-POLICY_LPT_SPLIT = 2  # load-aware assignment of equally split pairs (with Fair-Copying)
+POLICY_NAIVE = 0
+POLICY_LPT = 1
+POLICY_LPT_SPLIT = 2
+POLICY_FAIR = 3
 
 
 @dataclass(frozen=True)
 class Params:
-    n_slots: int = 512
-    tile: int = 64
-    min_chunk: int = 256
-    max_split: int = 128
+    n_slots: int = 256
+    tile: int = 16
+    min_chunk: int = 64
+    max_split: int = 256
     oversub: int = 2
-    overhead_tokens: int = 64
-    policy: int = POLICY_LPT_SPLIT
+    overhead_tokens: int = 32
+    policy: int = POLICY_FAIR
 
 
 @dataclass(frozen=True)
 class Item:
+    row: int          # first K/V row: off[b][h] + tok_begin
+    tok_count: int
     b: int
     h: int
     tok_begin: int
-    tok_count: int
-    chunk: int
     n_chunks: int
-    slot: int
-    part: int
+    part: int         # part_base[pair] + chunk index
 
     def astuple(self) -> Tuple[int, ...]:
-        return (self.b, self.h, self.tok_begin, self.tok_count, self.chunk, self.n_chunks,
-                self.slot, self.part)
+        return (self.row, self.tok_count, self.b, self.h, self.tok_begin, self.n_chunks, self.part)
 
 
 @dataclass(frozen=True)
@@ -71,106 +80,147 @@ def _ceil_div(a: int, b: int) -> int:
     return (a + b - 1) // b
 
 
-def validate(B: int, Hkv: int, lens, p: Params) -> None:
+def validate(B: int, Hkv: int, lens, offs, p: Params) -> None:
     if B <= 0 or Hkv <= 0:
         raise ValueError("B and Hkv must be positive")
-    if len(lens) != B * Hkv:
-        raise ValueError("lens must have B*Hkv entries")
+    if len(lens) != B * Hkv or len(offs) != B * Hkv:
+        raise ValueError("lens and offs must have B*Hkv entries")
     if any(int(x) < 0 for x in lens):
         raise ValueError("negative length")
+    if any(int(o) < 0 for o, n in zip(offs, lens) if int(n) > 0):
+        raise ValueError("negative offset")
     if p.n_slots < 1 or p.tile < 1 or p.max_split < 1 or p.oversub < 1:
         raise ValueError("n_slots, tile, max_split, oversub must be >= 1")
     if p.min_chunk < p.tile or p.min_chunk % p.tile != 0:
         raise ValueError("min_chunk must be a positive multiple of tile")
     if p.overhead_tokens < 0:
         raise ValueError("overhead_tokens must be >= 0")
-    if p.policy not in (POLICY_NAIVE, POLICY_LPT, POLICY_LPT_SPLIT):
+    if p.policy not in (POLICY_NAIVE, POLICY_LPT, POLICY_LPT_SPLIT, POLICY_FAIR):
         raise ValueError("unknown policy")
 
 
-def plan(lens, B: int, Hkv: int, p: Params):
-    """lens: flat sequence of B*Hkv ints in (b, h) order.
+def plan(lens, offs, B: int, Hkv: int, p: Params):
+    """lens, offs: flat sequences of B*Hkv ints in (b, h) order (tokens, first row).
 
-    Returns (items, slot_ptr, slot_items, part_base, summary):
-      items      work list in execution order,
-      slot_ptr   CSR pointer [n_slots+1] over items grouped by slot,
-      slot_items indices into `items`, grouped by slot, list order kept inside a slot,
-      part_base  [B*Hkv+1] running count of chunks before each pair (CSR over pairs),
-      summary    totals and the largest / smallest slot load (idle slots count as 0).
+    Returns (items, slot_ptr, part_base, summary):
+      items      work list grouped by slot; inside a slot, the order the slot runs them,
+      slot_ptr   [n_slots+1]: slot j runs items[slot_ptr[j] : slot_ptr[j+1]],
+      part_base  [B*Hkv+1]: running count of chunks before each pair,
+      summary    totals and the largest / smallest slot load (an idle slot counts 0).
     """
     lens = [int(x) for x in lens]
-    validate(B, Hkv, lens, p)
+    offs = [int(x) for x in offs]
+    validate(B, Hkv, lens, offs, p)
     n_pairs = B * Hkv
     total = sum(lens)
+    S, ov = p.n_slots, p.overhead_tokens
 
     def up(x: int) -> int:
         return _ceil_div(x, p.tile) * p.tile
 
-    # -- how many equal chunks each pair is cut into (the W / copies rule) ------------
-    if p.policy == POLICY_LPT_SPLIT:
-        target = max(p.min_chunk, up(_ceil_div(total, p.n_slots * p.oversub)))
-    else:
-        target = None  # never split
+    # pieces: (pair, tok_begin, tok_count, chunk index); slots: list of piece lists
+    slots: List[List[Tuple[int, int, int, int]]] = [[] for _ in range(S)]
+    n_chunks_of = [0] * n_pairs
 
-    chunks: List[Tuple[int, int, int, int, int, int]] = []   # (b,h,t0,n,chunk,n_chunks)
-    part_base = [0] * (n_pairs + 1)
-    for pair in range(n_pairs):
-        n = lens[pair]
-        b, h = divmod(pair, Hkv)
-        r_final = 0
-        if n > 0:
-            if target is None:
-                r = 1
-            else:
-                r = min(p.max_split, _ceil_div(n, target))
-            cs = up(_ceil_div(n, r))
+    if p.policy == POLICY_FAIR:
+        # One line of all pairs in (b, h) order, cut into S pieces of equal cost.  When a slot
+        # is opened its budget is the cost still to place divided by the slots still unopened
+        # (an item is counted as overhead for every pair still unfinished and every slot still
+        # to come), so slack or excess of one slot is spread over the later ones.  A pair that
+        # does not fit continues in the next slot, cut at a tile boundary.  No piece smaller than
+        # min_chunk is made: the slot is overfilled with the whole rest of the pair if that
+        # excess is smaller than the room it would otherwise leave unused, else it is closed.
+        # The last slot takes whatever is left.
+        tokens_left, pairs_left = total, n_pairs
+
+        def budget_for(j: int) -> int:
+            open_slots = S - j
+            return _ceil_div(tokens_left + ov * (pairs_left + open_slots), open_slots)
+
+        j = 0
+        room = budget_for(0)
+        for pair in range(n_pairs):
+            left, begin, c = lens[pair], 0, 0
+            if left == 0:
+                if room < ov and j < S - 1:
+                    j += 1
+                    room = budget_for(j)
+                slots[j].append((pair, 0, 0, 0))
+                room -= ov
+                c = 1
+            while left > 0:
+                last_slot = j == S - 1
+                last_copy = c == p.max_split - 1            # eq. 3: no further copy allowed
+                fit = max(0, (room - ov) // p.tile * p.tile)  # whole tiles that still fit here
+                if last_slot or last_copy or left <= fit:
+                    take = left
+                elif fit >= p.min_chunk and left - fit >= p.min_chunk:
+                    take = fit                               # cut: neither piece is tiny
+                elif left - fit <= fit:
+                    take = left                              # a small overfill beats unused room
+                else:                                        # too little room: close this slot
+                    j += 1
+                    room = budget_for(j)
+                    continue
+                slots[j].append((pair, begin, take, c))
+                room -= take + ov
+                begin, left, c = begin + take, left - take, c + 1
+                tokens_left -= take
+                if left > 0 and j < S - 1:                   # slot is full: go on in the next
+                    j += 1
+                    room = budget_for(j)
+            n_chunks_of[pair] = c
+            pairs_left -= 1
+    else:
+        if p.policy == POLICY_LPT_SPLIT:
+            target = max(p.min_chunk, up(_ceil_div(total, S * p.oversub)))
+        else:
+            target = None
+        pieces: List[Tuple[int, int, int, int]] = []
+        for pair in range(n_pairs):
+            n = lens[pair]
+            if n == 0:
+                pieces.append((pair, 0, 0, 0))
+                n_chunks_of[pair] = 1
+                continue
+            r = 1 if target is None else min(p.max_split, _ceil_div(n, target))
+            cs = up(_ceil_div(n, r))                       # W / copies, in whole tiles
             r_final = _ceil_div(n, cs)
             for c in range(r_final):
-                t0 = c * cs
-                chunks.append((b, h, t0, min(cs, n - t0), c, r_final))
-        part_base[pair + 1] = part_base[pair] + r_final
+                pieces.append((pair, c * cs, min(cs, n - c * cs), c))
+            n_chunks_of[pair] = r_final
+        if p.policy == POLICY_NAIVE:
+            for idx, pc in enumerate(pieces):
+                slots[idx % S].append(pc)
+        else:
+            load = [0] * S
+            for pc in sorted(pieces, key=lambda x: (-x[2], x[0], x[3])):
+                j = min(range(S), key=lambda s: (load[s], s))
+                load[j] += pc[2] + ov
+                slots[j].append(pc)
 
-    # -- order and assignment --------------------------------------------------------
-    load = [0] * p.n_slots
+    part_base = [0] * (n_pairs + 1)
+    for pair in range(n_pairs):
+        part_base[pair + 1] = part_base[pair] + n_chunks_of[pair]
+
     items: List[Item] = []
-    if p.policy == POLICY_NAIVE:
-        order = chunks  # already ascending (b, h); one chunk per pair
-        for idx, (b, h, t0, n, c, nc) in enumerate(order):
-            j = idx % p.n_slots
-            load[j] += n + p.overhead_tokens
-            items.append(Item(b, h, t0, n, c, nc, j, part_base[b * Hkv + h] + c))
-    else:
-        order = sorted(chunks, key=lambda x: (-x[3], x[0], x[1], x[4]))
-        for (b, h, t0, n, c, nc) in order:
-            j = min(range(p.n_slots), key=lambda s: (load[s], s))
-            load[j] += n + p.overhead_tokens
-            items.append(Item(b, h, t0, n, c, nc, j, part_base[b * Hkv + h] + c))
+    slot_ptr = [0] * (S + 1)
+    loads = []
+    for j in range(S):
+        for (pair, begin, count, c) in slots[j]:
+            b, h = divmod(pair, Hkv)
+            items.append(Item(offs[pair] + begin, count, b, h, begin, n_chunks_of[pair], part_base[pair] + c))
+        slot_ptr[j + 1] = len(items)
+        loads.append(sum(pc[2] + ov for pc in slots[j]))
 
-    # -- CSR by slot (stable) --------------------------------------------------------
-    slot_ptr = [0] * (p.n_slots + 1)
-    for it in items:
-        slot_ptr[it.slot + 1] += 1
-    for j in range(p.n_slots):
-        slot_ptr[j + 1] += slot_ptr[j]
-    slot_items = _stable_by_slot(items, p.n_slots)
-
-    summary = Summary(total, max(load), min(load), len(items), part_base[n_pairs])
-    return items, slot_ptr, slot_items, part_base, summary
-
-
-def _stable_by_slot(items, n_slots):
-    buckets = [[] for _ in range(n_slots)]
-    for i, it in enumerate(items):
-        buckets[it.slot].append(i)
-    return [i for bkt in buckets for i in bkt]
+    summary = Summary(total, max(loads), min(loads), len(items), part_base[n_pairs])
+    return items, slot_ptr, part_base, summary
 
 
 # ---- figures of merit, straight from the paper's definitions ------------------------
-def slot_loads(items, n_slots: int, overhead_tokens: int):
-    load = [0] * n_slots
-    for it in items:
-        load[it.slot] += it.tok_count + overhead_tokens
-    return load
+def slot_loads(items, slot_ptr, overhead_tokens: int):
+    return [sum(it.tok_count + overhead_tokens for it in items[slot_ptr[j]:slot_ptr[j + 1]])
+            for j in range(len(slot_ptr) - 1)]
 
 
 def delta(loads) -> int:

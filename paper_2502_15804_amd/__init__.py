@@ -18,15 +18,15 @@ LIB_PATH = os.path.join(_HERE, "libfairkv.so")
 
 FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, FAIRKV_EHIP = 0, -1, -2, -3, -4, -5
 FAIRKV_BF16, FAIRKV_F32 = 0, 1
-FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT = 0, 1, 2
+FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
            "fairkv_strerror", "fairkv_version")
 
 
 class fairkv_item(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in
-                ("b", "h", "tok_begin", "tok_count", "chunk", "n_chunks", "slot", "part")]
+    _fields_ = [("row", ctypes.c_int64)] + [(n, ctypes.c_int32) for n in
+                                            ("tok_count", "b", "h", "tok_begin", "n_chunks", "part")]
 
 
 class fairkv_plan_params(ctypes.Structure):
@@ -39,7 +39,7 @@ class fairkv_plan_summary(ctypes.Structure):
                 ("min_slot_load", ctypes.c_int64), ("n_items", ctypes.c_int32), ("n_parts", ctypes.c_int32)]
 
 
-ITEM_DTYPE = np.dtype([(n, np.int32) for n, _ in fairkv_item._fields_])
+ITEM_DTYPE = np.dtype([("row", np.int64)] + [(n, np.int32) for n, _ in fairkv_item._fields_[1:]])
 assert ITEM_DTYPE.itemsize == ctypes.sizeof(fairkv_item) == 32
 
 
@@ -64,12 +64,12 @@ def lib() -> ctypes.CDLL:
         L.fairkv_default_params.restype = ctypes.c_int
         L.fairkv_default_params.argtypes = [ctypes.POINTER(fairkv_plan_params), i32]
         L.fairkv_plan.restype = ctypes.c_int
-        L.fairkv_plan.argtypes = [vp, i32, i32, ctypes.POINTER(fairkv_plan_params), vp, i32, vp, vp,
+        L.fairkv_plan.argtypes = [vp, i64p, i32, i32, ctypes.POINTER(fairkv_plan_params), vp, i32, vp, vp,
                                   ctypes.POINTER(fairkv_plan_summary)]
         L.fairkv_workspace_bytes.restype = ctypes.c_size_t
-        L.fairkv_workspace_bytes.argtypes = [i32, i32, i32]
+        L.fairkv_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.fairkv_decode_attn.restype = ctypes.c_int
-        L.fairkv_decode_attn.argtypes = [vp, vp, vp, i64p, vp, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp,
+        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp,
                                          i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
@@ -101,7 +101,7 @@ def fairkv_default_params(n_compute_units: int, **overrides) -> fairkv_plan_para
 @dataclass
 class Plan:
     """Host-side result of fairkv_plan (numpy arrays, ready to copy to the device)."""
-    items: np.ndarray        # structured array of fairkv_item, execution order
+    items: np.ndarray        # structured array of fairkv_item, grouped by slot
     slot_ptr: np.ndarray     # int32 [n_slots+1]
     part_base: np.ndarray    # int32 [B*Hkv+1]
     summary: fairkv_plan_summary
@@ -115,75 +115,83 @@ class Plan:
     def n_parts(self) -> int:
         return int(self.summary.n_parts)
 
+    @property
+    def n_slots(self) -> int:
+        return int(self.params.n_slots)
 
-def fairkv_plan(lens, B: int, Hkv: int, params: fairkv_plan_params) -> Plan:
+    def slot_loads(self) -> np.ndarray:
+        cost = self.items["tok_count"].astype(np.int64) + int(self.params.overhead_tokens)
+        csum = np.concatenate([[0], np.cumsum(cost)])
+        return csum[self.slot_ptr[1:]] - csum[self.slot_ptr[:-1]]
+
+
+def fairkv_plan(lens, off, B: int, Hkv: int, params: fairkv_plan_params) -> Plan:
     """Two calls into the library: one to size the work list, one to fill it."""
     lens = np.ascontiguousarray(np.asarray(lens).reshape(-1), dtype=np.int32)
-    if lens.size != int(B) * int(Hkv):
-        raise ValueError("lens must have B*Hkv entries")
+    off = np.ascontiguousarray(np.asarray(off).reshape(-1), dtype=np.int64)
+    if lens.size != int(B) * int(Hkv) or off.size != lens.size:
+        raise ValueError("lens and off must have B*Hkv entries")
     L = lib()
     summary = fairkv_plan_summary()
     n_slots = max(int(params.n_slots), 0)
     slot_ptr = np.zeros(n_slots + 1, dtype=np.int32)
     part_base = np.zeros(int(B) * int(Hkv) + 1, dtype=np.int32)
-    rc = L.fairkv_plan(lens.ctypes.data, B, Hkv, ctypes.byref(params), None, 0,
+    rc = L.fairkv_plan(lens.ctypes.data, off.ctypes.data, B, Hkv, ctypes.byref(params), None, 0,
                        slot_ptr.ctypes.data, part_base.ctypes.data, ctypes.byref(summary))
     if rc not in (FAIRKV_OK, FAIRKV_ECAP):
         raise FairKVError(rc, "fairkv_plan")
     items = np.zeros(int(summary.n_items), dtype=ITEM_DTYPE)
     if summary.n_items > 0:
-        rc = L.fairkv_plan(lens.ctypes.data, B, Hkv, ctypes.byref(params), items.ctypes.data, items.size,
-                           slot_ptr.ctypes.data, part_base.ctypes.data, ctypes.byref(summary))
+        rc = L.fairkv_plan(lens.ctypes.data, off.ctypes.data, B, Hkv, ctypes.byref(params), items.ctypes.data,
+                           items.size, slot_ptr.ctypes.data, part_base.ctypes.data, ctypes.byref(summary))
         if rc != FAIRKV_OK:
             raise FairKVError(rc, "fairkv_plan")
     return Plan(items, slot_ptr, part_base, summary, params)
 
 
-def fairkv_workspace_bytes(n_parts: int, G: int, D: int) -> int:
-    return int(lib().fairkv_workspace_bytes(int(n_parts), int(G), int(D)))
+def fairkv_workspace_bytes(n_parts: int, n_pairs: int, G: int, D: int) -> int:
+    return int(lib().fairkv_workspace_bytes(int(n_parts), int(n_pairs), int(G), int(D)))
 
 
 def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def fairkv_decode_attn(q, k, v, off, lens, items, part_base, n_parts, workspace, out, lse, scale, stream=None):
+def fairkv_decode_attn(q, k, v, items, slot_ptr, part_base, n_parts, workspace, out, lse, scale, Hkv, stream=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
 
-    All arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
-    off int64 [B,Hkv]; lens int32 [B,Hkv]; items uint8/int32 view of the plan's item array
-    (n_items * 32 bytes); part_base int32 [B*Hkv+1]; workspace uint8; out [B,Hq,D] float32 or
-    bfloat16; lse float32 [B,Hq] or None.  Nothing is allocated or synchronised here.
+    All tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
+    items: uint8 view of the plan's item array (n_items * 32 bytes); slot_ptr int32 [n_slots+1];
+    part_base int32 [B*Hkv+1]; workspace uint8, zero-filled before its first use; out [B,Hq,D]
+    float32 or bfloat16; lse float32 [B,Hq] or None.  Nothing is allocated or synchronised here.
     """
     import torch
 
     B, Hq, D = q.shape
-    Hkv = lens.shape[1]
     dt = {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}
     if q.dtype not in dt or k.dtype != q.dtype or v.dtype != q.dtype or out.dtype not in dt:
         raise TypeError("q/k/v must share bf16 or fp32; out must be bf16 or fp32")
-    for name, t in (("q", q), ("k", k), ("v", v), ("off", off), ("lens", lens), ("items", items),
+    for name, t in (("q", q), ("k", k), ("v", v), ("items", items), ("slot_ptr", slot_ptr),
                     ("part_base", part_base), ("workspace", workspace), ("out", out), ("lse", lse)):
         if t is None:
             continue
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous device tensor")
-    if off.dtype != torch.int64 or lens.dtype != torch.int32 or part_base.dtype != torch.int32:
-        raise TypeError("off must be int64; lens and part_base int32")
+    if slot_ptr.dtype != torch.int32 or part_base.dtype != torch.int32:
+        raise TypeError("slot_ptr and part_base must be int32")
     if lse is not None and lse.dtype != torch.float32:
         raise TypeError("lse must be float32")
-    if k.shape[1] != D or v.shape != k.shape or tuple(off.shape) != tuple(lens.shape) or lens.shape[0] != B:
+    if k.shape[1] != D or v.shape != k.shape:
         raise ValueError("shape mismatch")
-    if part_base.numel() != B * Hkv + 1 or tuple(out.shape) != (B, Hq, D):
+    if part_base.numel() != B * Hkv + 1 or tuple(out.shape) != (B, Hq, D) or slot_ptr.numel() < 2:
         raise ValueError("shape mismatch")
     item_bytes = items.numel() * items.element_size()
     if item_bytes % 32 != 0:
         raise ValueError("items must be a whole number of 32-byte records")
-    n_items = item_bytes // 32
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     rc = lib().fairkv_decode_attn(
-        _ptr(q), _ptr(k), _ptr(v), _ptr(off), _ptr(lens), _ptr(items) if n_items else None, n_items,
+        _ptr(q), _ptr(k), _ptr(v), _ptr(items), item_bytes // 32, _ptr(slot_ptr), slot_ptr.numel() - 1,
         _ptr(part_base), int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(out), _ptr(lse), B, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
         ctypes.c_void_p(stream.cuda_stream))

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfairkv.so")
 SOURCES = [os.path.join(CSRC, "fairkv_api.hip"), os.path.join(CSRC, "fairkv_plan.cpp")]
-HEADERS = [os.path.join(ROOT, "include", "fairkv.h")] + [os.path.join(CSRC, h) for h in ("common.h", "decode_mfma.h", "decode_valu.h", "merge.h")]
+HEADERS = [os.path.join(ROOT, "include", "fairkv.h")] + [os.path.join(CSRC, h) for h in ("common.h", "decode_mfma.h", "decode_valu.h")]
 
 
 def is_stale() -> bool:

@@ -52,17 +52,31 @@ __device__ __forceinline__ void store_out(void *out, int out_dtype, size_t idx, 
         static_cast<uint16_t *>(out)[idx] = f32_to_bf16_rne(x);
 }
 
+// Partial results travel between workgroups that may sit on different XCDs, whose L2 caches
+// are not coherent with each other.  Agent-scope relaxed atomics are plain 4-byte stores and
+// loads that go through to the level all XCDs share, without the cache-wide write-back and
+// invalidate that a device fence costs (measured: tens of microseconds per launch).
+__device__ __forceinline__ void publish_f32(float *p, float x)
+{
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float fetch_f32(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 struct DecodeArgs {
     const void *q, *k, *v;
-    const int64_t *off;
-    const int32_t *len;
-    const fairkv_item *items;
-    float *part_o;    // [n_parts][G][D]   unnormalised outputs relative to the item's maximum
-    float *part_ml;   // [n_parts][G][2]   (maximum in log2 units, sum of weights)
+    const fairkv_item *items;   // grouped by slot
+    const int32_t *slot_ptr;    // [n_slots + 1]
+    const int32_t *part_base;   // [B*Hkv + 1]
+    float *part_o;              // [n_parts][G][D]   unnormalised outputs relative to the item's maximum
+    float *part_ml;             // [n_parts][G][2]   (maximum in log2 units, sum of weights)
+    int32_t *arrivals;          // [B*Hkv] items of a cut pair that have delivered their partial; 0 between calls
     void *out;
     float *lse;
-    int32_t B, Hq, Hkv, out_dtype;
-    float scale_log2;  // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
+    int32_t B, Hq, Hkv, out_dtype, n_parts;
+    float scale_log2;           // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
 };
 
 // Layout facts shared by the stages.  A row of K or V is LPR 16-byte pieces; one wave-wide
@@ -80,16 +94,80 @@ struct Geo {
 };
 
 
-// Workgroup epilogue.  st_o [kWaves][G][D] and st_ml [kWaves][G][2] in LDS hold each wave's
-// unnormalised output, running maximum (log2 units) and weight sum.  Combines them with
-//   m* = max_w m_w,  l* = sum_w l_w 2^(m_w - m*),  o* = sum_w o_w 2^(m_w - m*)
-// and writes out = o*/l* and lse when the item is the whole pair, else the partial (m*, l*, o*).
+constexpr int kMergeBatch = 8;   // partials of a cut pair fetched at once by the merging workgroup
+
+// Combine the n_chunks partials of a pair (the log-sum-exp merge):
+//   m* = max_c m_c,  l* = sum_c l_c 2^(m_c - m*),  out = sum_c o_c 2^(m_c - m*) / l*.
+// Exact in real arithmetic, so a cut pair gives what the whole pair would.  Called by all
+// threads of one workgroup; a thread owns four consecutive coordinates of one query head and
+// fetches up to kMergeBatch partials at once so that their latencies overlap.
 template <int D, int G>
-__device__ __forceinline__ void workgroup_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
-                                                   const float *st_ml)
+__device__ __forceinline__ void merge_pair(const DecodeArgs &a, int b, int h, int p0, int nc)
+{
+    constexpr int D4 = D / 4;
+    for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
+        const int g = idx / D4, d = (idx % D4) * 4;
+        float m_star = -INFINITY, l_star = 0.f;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
+            float4 o[kMergeBatch];
+            float2 ml[kMergeBatch];
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                const int c = min(c0 + j, nc - 1);   // past the end: re-read the last one, weight 0 below
+                const size_t pg = static_cast<size_t>(p0 + c) * G + g;
+                ml[j].x = fetch_f32(a.part_ml + pg * 2);
+                ml[j].y = fetch_f32(a.part_ml + pg * 2 + 1);
+                o[j].x = fetch_f32(a.part_o + pg * D + d);
+                o[j].y = fetch_f32(a.part_o + pg * D + d + 1);
+                o[j].z = fetch_f32(a.part_o + pg * D + d + 2);
+                o[j].w = fetch_f32(a.part_o + pg * D + d + 3);
+            }
+            float m_new = m_star;
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j)
+                if (c0 + j < nc) m_new = fmaxf(m_new, ml[j].x);
+            const float keep = m_star == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_star - m_new);
+            l_star *= keep;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] *= keep;
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                const bool live = c0 + j < nc && ml[j].x != -INFINITY;
+                const float f = live ? __builtin_amdgcn_exp2f(ml[j].x - m_new) : 0.f;
+                l_star = fmaf(ml[j].y, f, l_star);
+                acc[0] = fmaf(o[j].x, f, acc[0]);
+                acc[1] = fmaf(o[j].y, f, acc[1]);
+                acc[2] = fmaf(o[j].z, f, acc[2]);
+                acc[3] = fmaf(o[j].w, f, acc[3]);
+            }
+            m_star = m_new;
+        }
+        const size_t oi = (static_cast<size_t>(b) * a.Hq + h * G + g) * D + d;
+        const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) store_out(a.out, a.out_dtype, oi + e, acc[e] * inv);
+        if (d == 0 && a.lse)
+            a.lse[b * a.Hq + h * G + g] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
+    }
+}
+
+// End of one item, called by all threads of the workgroup after every wave has put its
+// unnormalised output, running maximum (log2 units) and weight sum into st_o [kWaves][G][D]
+// and st_ml [kWaves][G][2] in LDS.  Folds the waves:
+//   m* = max_w m_w,  l* = sum_w l_w 2^(m_w - m*),  o* = sum_w o_w 2^(m_w - m*).
+// An item that is a whole pair writes out = o*/l* and lse.  An item of a cut pair publishes
+// its partial (m*, l*, o*), waits until the stores are acknowledged, and counts itself in; the
+// workgroup that finds itself last merges all partials of the pair and puts the counter back
+// to zero.
+// `flag` is one int in LDS.  Ends with a barrier, so st_o/st_ml may be reused at once.
+template <int D, int G>
+__device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
+                                              const float *st_ml, int *flag)
 {
     const int b = it.b, h = it.h;
     const bool whole_pair = it.n_chunks == 1;
+    __syncthreads();
     for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
         const int g = idx / D, d = idx % D;
         float m_star = -INFINITY;
@@ -110,13 +188,30 @@ __device__ __forceinline__ void workgroup_epilogue(const DecodeArgs &a, const fa
                 a.lse[b * a.Hq + h * G + g] =
                     l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         } else {
-            a.part_o[(static_cast<size_t>(it.part) * G + g) * D + d] = acc;
+            publish_f32(a.part_o + (static_cast<size_t>(it.part) * G + g) * D + d, acc);
             if (d == 0) {
-                a.part_ml[(static_cast<size_t>(it.part) * G + g) * 2 + 0] = m_star;
-                a.part_ml[(static_cast<size_t>(it.part) * G + g) * 2 + 1] = l_star;
+                publish_f32(a.part_ml + (static_cast<size_t>(it.part) * G + g) * 2 + 0, m_star);
+                publish_f32(a.part_ml + (static_cast<size_t>(it.part) * G + g) * 2 + 1, l_star);
             }
         }
     }
+    if (whole_pair) {
+        __syncthreads();
+        return;
+    }
+    const int pair = b * a.Hkv + h;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have reached the shared level ...
+    __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
+    if (threadIdx.x == 0)
+        *flag = __hip_atomic_fetch_add(a.arrivals + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == it.n_chunks - 1;
+    __syncthreads();
+    if (*flag) {   // every partial of the pair was published before its workgroup counted in
+        const int p0 = a.part_base[pair];
+        if (p0 >= 0 && p0 + it.n_chunks <= a.n_parts) merge_pair<D, G>(a, b, h, p0, it.n_chunks);
+        if (threadIdx.x == 0)   // ready for the next call on this workspace
+            __hip_atomic_store(a.arrivals + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
 }
 
 }  // namespace fairkv

@@ -17,7 +17,9 @@
 //
 // Data path.  K and V rows go from HBM straight into LDS (global_load_lds_dwordx4, no
 // registers), each wave filling its own ring of kStages tiles, so up to kStages-1 tiles
-// per wave are in flight while one is being consumed.  16-byte pieces are stored
+// per wave are in flight while one is being consumed.  The workgroup is persistent: it
+// walks the items the planner gave its slot, and a wave's ring runs on into the next item
+// while the current one is being finished, so only the first tile of a slot waits for HBM.  16-byte pieces are stored
 // XOR-swizzled (the swizzle is applied to the global address a lane fetches, since the
 // LDS slot of a lane is fixed) so that the row-per-lane reads of K and the transposing
 // reads of V (ds_read_b64_tr_b16) spread over all banks.
@@ -55,6 +57,14 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// LDS table of the slot's items: what the waves need of a fairkv_item, 16 bytes each.
+struct ItemRef {
+    int64_t row;
+    int32_t n;
+    int32_t valid;   // 0: the item does not belong to this problem and is skipped
+};
+constexpr int kTable = 64;   // items per table fill; longer slot lists are walked in batches
+
 template <int D, int G>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
@@ -71,47 +81,36 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     constexpr int NDB = D / 16;              // 16-wide d blocks of the output
 
     __shared__ __attribute__((aligned(1024))) char lds[kWaves * kStages * STAGEB];
+    __shared__ __attribute__((aligned(16))) float st_o[kWaves * G * D];
+    __shared__ float st_ml[kWaves * G * 2];
+    __shared__ __attribute__((aligned(16))) ItemRef table[kTable];
+    __shared__ int flag;
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, so loop control is scalar
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: loop control is scalar
     const int l16 = lane & 15;      // head in B/C operands, token row in the K operand, d in the V operand
     const int lq = lane >> 4;       // which quarter of the contraction index this lane feeds
 
-    const fairkv_item it = a.items[blockIdx.x];
-    const int b = it.b, h = it.h;
-    if (b < 0 || b >= a.B || h < 0 || h >= a.Hkv || it.tok_begin < 0 || it.part < 0) return;
-    const int pair = b * a.Hkv + h;
-    const int64_t row0 = a.off[pair] + it.tok_begin;
-    int n = min(it.tok_count, a.len[pair] - it.tok_begin);
-    n = max(n, 0);
-    const int n_tiles = (n + kTok - 1) / kTok;
-    const int my_tiles = n_tiles > wave ? (n_tiles - wave + kWaves - 1) / kWaves : 0;   // tiles wave, wave+4, ...
-
-    const char *kbase = static_cast<const char *>(a.k) + row0 * ROWB;
-    const char *vbase = static_cast<const char *>(a.v) + row0 * ROWB;
-    char *ring = lds + wave * (kStages * STAGEB);
-    const uint32_t ring_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(ring)));
-
-    // q as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8]; heads >= G are zero.
-    bf16x8_t qb[NSL];
-    {
-        const uint4 *qrow = reinterpret_cast<const uint4 *>(static_cast<const char *>(a.q) +
-                                                            (static_cast<size_t>(b) * a.Hq + h * G + min(l16, G - 1)) * ROWB);
-#pragma unroll
-        for (int s = 0; s < NSL; ++s) {
-            uint4 w = qrow[4 * s + lq];
-            if (l16 >= G) w = make_uint4(0u, 0u, 0u, 0u);
-            qb[s] = __builtin_bit_cast(bf16x8_t, w);
-        }
-    }
-
-    // Fetch of one tile into one stage.  Lane j of load i fills LDS slot (row i*RPI + j/PPR,
-    // column j%PPR); the piece it fetches is column ^ swizzle(row).  Rows past the end of the
-    // item re-read the last valid row, so that every stage costs exactly LOADS instructions.
+    const int i_begin = a.slot_ptr[blockIdx.x], i_end = a.slot_ptr[blockIdx.x + 1];
+    const uint32_t ring_lds =
+        static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(lds))) + wave * (kStages * STAGEB);
+    const char *ring = lds + wave * (kStages * STAGEB);
     const int ld_row = lane / PPR, ld_col = lane % PPR;
-    auto fetch = [&](int t, int stage) {
+
+    // tiles of an n-token item that fall to this wave: tiles wave, wave + kWaves, ...
+    auto tiles_of = [&](int n) {
+        const int n_tiles = (n + kTok - 1) / kTok;
+        return n_tiles > wave ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
+    };
+
+    // Fetch of this wave's t-th tile of an item into one stage.  Lane j of load i fills LDS slot
+    // (row i*RPI + j/PPR, column j%PPR); the piece it fetches is column ^ swizzle(row).  Rows past
+    // the end of the item re-read its last row, so that every stage costs exactly LOADS loads.
+    auto fetch = [&](int64_t row, int n, int t, int stage) {
         const int tok0 = (wave + t * kWaves) * kTok;
-        const int last = n - 1 - tok0;           // last valid row of this tile, relative
+        const int last = n - 1 - tok0;
+        const char *kbase = static_cast<const char *>(a.k) + (row + tok0) * ROWB;
+        const char *vbase = static_cast<const char *>(a.v) + (row + tok0) * ROWB;
         const uint32_t kst = ring_lds + stage * STAGEB;
         const uint32_t vst = kst + TILEB;
 #pragma unroll
@@ -120,112 +119,164 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             const int rc = min(r, last);
             const int kcol = ld_col ^ (r % PPR);
             const int vcol = ld_col ^ ((2 * r) % PPR);
-            load16_to_lds(kbase + static_cast<size_t>(tok0 + rc) * ROWB + kcol * 16, kst + i * 1024);
-            load16_to_lds(vbase + static_cast<size_t>(tok0 + rc) * ROWB + vcol * 16, vst + i * 1024);
+            load16_to_lds(kbase + rc * ROWB + kcol * 16, kst + i * 1024);
+            load16_to_lds(vbase + rc * ROWB + vcol * 16, vst + i * 1024);
         }
     };
 
-    f32x4_t o[NDB];
-#pragma unroll
-    for (int nb = 0; nb < NDB; ++nb) o[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
-
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-        if (s < my_tiles) fetch(s, s);
-
-    for (int t = 0; t < my_tiles; ++t) {
-        const int stage = t % kStages;
-        if (t + kStages - 1 < my_tiles) fetch(t + kStages - 1, (t + kStages - 1) % kStages);
-        // tile t is complete once at most the loads of the later tiles are outstanding
-        const int later = min(kStages - 1, my_tiles - 1 - t);
-        if (later >= 3) wait_vmcnt<3 * LOADS>();
-        else if (later == 2) wait_vmcnt<2 * LOADS>();
-        else if (later == 1) wait_vmcnt<LOADS>();
-        else wait_vmcnt<0>();
-        static_assert(kStages == 4, "the wait ladder above is written for four stages");
-
-        const char *kst = ring + stage * STAGEB;
-        const char *vst = kst + TILEB;
-        const int tok0 = (wave + t * kWaves) * kTok;
-        const int nv = min(kTok, n - tok0);
-
-        // ---- scores: S^T[token 4 lq + i][head l16] -----------------------------------------
-        f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+    // q of an item as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8]; heads >= G are zero.
+    auto load_q = [&](const fairkv_item &it, bf16x8_t (&qb)[NSL]) {
+        const uint4 *qrow = reinterpret_cast<const uint4 *>(
+            static_cast<const char *>(a.q) + (static_cast<size_t>(it.b) * a.Hq + it.h * G + min(l16, G - 1)) * ROWB);
 #pragma unroll
         for (int s = 0; s < NSL; ++s) {
-            const int piece = 4 * s + lq;
-            const uint4 kw = *reinterpret_cast<const uint4 *>(kst + l16 * ROWB + ((piece ^ (l16 % PPR)) * 16));
-            sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw), qb[s], sacc, 0, 0, 0);
+            uint4 w = qrow[4 * s + lq];
+            if (l16 >= G) w = make_uint4(0u, 0u, 0u, 0u);
+            qb[s] = __builtin_bit_cast(bf16x8_t, w);
         }
+    };
 
-        // ---- online softmax, all in this lane's head ----------------------------------------
-        float sv[4];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sv[i] = (4 * lq + i) < nv ? sacc[i] * a.scale_log2 : -INFINITY;
-            mx = fmaxf(mx, sv[i]);
+    for (int batch = i_begin; batch < i_end; batch += kTable) {
+        const int nb = min(kTable, i_end - batch);
+        __syncthreads();                      // nobody still reads the previous table
+        if (threadIdx.x < nb) {
+            const fairkv_item it = a.items[batch + threadIdx.x];
+            const bool ok = it.b >= 0 && it.b < a.B && it.h >= 0 && it.h < a.Hkv && it.row >= 0 && it.part >= 0 &&
+                            it.part < a.n_parts && it.n_chunks >= 1;
+            table[threadIdx.x] = ItemRef{it.row, ok ? max(it.tok_count, 0) : 0, ok ? 1 : 0};   // a foreign item reads nothing
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first tile
-        float p[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
-        const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
-        // the sum uses the rounded weights, so out is an exact convex combination of V rows
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) psum += static_cast<float>(pb[i]);
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
-#pragma unroll
-            for (int nb = 0; nb < NDB; ++nb)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o[nb][i] *= alpha;
-        }
+        __syncthreads();
 
-        // ---- O^T[d][head] += V^T P: transposing LDS read gives V[token 4 lq + i][16 nb + l16] ----
-        const int vrow = 4 * lq + (l16 >> 2);     // row this lane addresses for the transposing read
-        const int vsub = l16 & 3;                 // which 4 d's (8 bytes) of the 16-wide block
-#pragma unroll
-        for (int nb = 0; nb < NDB; ++nb) {
-            const int piece = 2 * nb + (vsub >> 1);
-            const char *src = vst + vrow * ROWB + ((piece ^ ((2 * vrow) % PPR)) * 16) + (vsub & 1) * 8;
-            i16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(src));
-            if (nv < kTok) {     // rows past the end hold a re-read row: keep inf/NaN in it from leaking in
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (4 * lq + i >= nv) vt[i] = 0;
+        // fetch cursor (runs ahead, possibly into later items) and the ring bookkeeping
+        int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0;
+        int f_n = __builtin_amdgcn_readfirstlane(table[0].n);
+        int f_tiles = tiles_of(f_n);
+        auto top_up = [&]() {
+            while (ahead < kStages && f_item < nb) {
+                if (f_t < f_tiles) {
+                    const int64_t row = table[f_item].row;
+                    fetch(row, f_n, f_t, f_stage);
+                    f_stage = (f_stage + 1) % kStages;
+                    ++f_t;
+                    ++ahead;
+                } else {
+                    ++f_item;
+                    f_t = 0;
+                    f_n = f_item < nb ? __builtin_amdgcn_readfirstlane(table[f_item].n) : 0;
+                    f_tiles = tiles_of(f_n);
+                }
             }
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, __builtin_bit_cast(i16x4_t, pb), o[nb], 0, 0, 0);
-        }
-    }
+        };
+        top_up();
 
-    // ---- fold the four token quarters of l, then the waves of the workgroup ----------------
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
+        bf16x8_t q_next[NSL];
+        if (__builtin_amdgcn_readfirstlane(table[0].valid)) load_q(a.items[batch], q_next);
 
-    __syncthreads();   // every wave has consumed its ring: reuse the memory for staging
-    float *st_o = reinterpret_cast<float *>(lds);      // [kWaves][G][D]
-    float *st_ml = st_o + kWaves * G * D;              // [kWaves][G][2]
-    static_assert(sizeof(float) * kWaves * G * (D + 2) <= sizeof(lds), "staging fits in the rings");
-    if (l16 < G) {
+        for (int ci = 0; ci < nb; ++ci) {
+            const fairkv_item it = a.items[batch + ci];
+            const int n = __builtin_amdgcn_readfirstlane(table[ci].n);
+            const int my_tiles = tiles_of(n);
+            bf16x8_t qb[NSL];
 #pragma unroll
-        for (int nb = 0; nb < NDB; ++nb)
-            *reinterpret_cast<float4 *>(st_o + (wave * G + l16) * D + 16 * nb + 4 * lq) =
-                make_float4(o[nb][0], o[nb][1], o[nb][2], o[nb][3]);
-        if (lq == 0) {
-            st_ml[(wave * G + l16) * 2 + 0] = m_run;
-            st_ml[(wave * G + l16) * 2 + 1] = l_run;
+            for (int s = 0; s < NSL; ++s) qb[s] = q_next[s];
+            if (ci + 1 < nb && __builtin_amdgcn_readfirstlane(table[ci + 1].valid))
+                load_q(a.items[batch + ci + 1], q_next);   // lands while this item streams
+
+            f32x4_t o[NDB];
+#pragma unroll
+            for (int nb_ = 0; nb_ < NDB; ++nb_) o[nb_] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            float m_run = -INFINITY, l_run = 0.f;
+
+            for (int t = 0; t < my_tiles; ++t) {
+                top_up();
+                // tile t is complete once at most the loads of the tiles fetched after it are outstanding
+                const int later = ahead - 1;
+                if (later >= 3) wait_vmcnt<3 * LOADS>();
+                else if (later == 2) wait_vmcnt<2 * LOADS>();
+                else if (later == 1) wait_vmcnt<LOADS>();
+                else wait_vmcnt<0>();
+                static_assert(kStages == 4, "the wait ladder above is written for four stages");
+
+                const char *kst = ring + c_stage * STAGEB;
+                const char *vst = kst + TILEB;
+                const int tok0 = (wave + t * kWaves) * kTok;
+                const int nv = min(kTok, n - tok0);
+
+                // ---- scores: S^T[token 4 lq + i][head l16] -----------------------------------------
+                f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < NSL; ++s) {
+                    const int piece = 4 * s + lq;
+                    const uint4 kw = *reinterpret_cast<const uint4 *>(kst + l16 * ROWB + ((piece ^ (l16 % PPR)) * 16));
+                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw), qb[s], sacc, 0, 0, 0);
+                }
+
+                // ---- online softmax, all in this lane's head ----------------------------------------
+                float sv[4];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    sv[i] = (4 * lq + i) < nv ? sacc[i] * a.scale_log2 : -INFINITY;
+                    mx = fmaxf(mx, sv[i]);
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first tile
+                float p[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
+                const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
+                // the sum uses the rounded weights, so out is an exact convex combination of V rows
+                float psum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) psum += static_cast<float>(pb[i]);
+                l_run = l_run * alpha + psum;
+                m_run = m_new;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+                    for (int nb_ = 0; nb_ < NDB; ++nb_)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[nb_][i] *= alpha;
+                }
+
+                // ---- O^T[d][head] += V^T P: transposing LDS read gives V[token 4 lq + i][16 nb + l16] ----
+                const int vrow = 4 * lq + (l16 >> 2);     // row this lane addresses for the transposing read
+                const int vsub = l16 & 3;                 // which 4 d's (8 bytes) of the 16-wide block
+#pragma unroll
+                for (int nb_ = 0; nb_ < NDB; ++nb_) {
+                    const int piece = 2 * nb_ + (vsub >> 1);
+                    const char *src = vst + vrow * ROWB + ((piece ^ ((2 * vrow) % PPR)) * 16) + (vsub & 1) * 8;
+                    i16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(src));
+                    if (nv < kTok) {     // rows past the end hold a re-read row: keep inf/NaN in it from leaking in
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (4 * lq + i >= nv) vt[i] = 0;
+                    }
+                    o[nb_] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, __builtin_bit_cast(i16x4_t, pb), o[nb_], 0, 0, 0);
+                }
+                c_stage = (c_stage + 1) % kStages;
+                --ahead;
+            }
+
+            // ---- fold the four token quarters of l, stage this wave's result, finish the item ------
+            l_run += __shfl_xor(l_run, 16, 64);
+            l_run += __shfl_xor(l_run, 32, 64);
+            if (l16 < G) {
+#pragma unroll
+                for (int nb_ = 0; nb_ < NDB; ++nb_)
+                    *reinterpret_cast<float4 *>(st_o + (wave * G + l16) * D + 16 * nb_ + 4 * lq) =
+                        make_float4(o[nb_][0], o[nb_][1], o[nb_][2], o[nb_][3]);
+                if (lq == 0) {
+                    st_ml[(wave * G + l16) * 2 + 0] = m_run;
+                    st_ml[(wave * G + l16) * 2 + 1] = l_run;
+                }
+            }
+            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G>(a, it, st_o, st_ml, &flag);
         }
+        wait_vmcnt<0>();   // nothing of this batch may still be landing in the rings
     }
-    __syncthreads();
-    workgroup_epilogue<D, G>(a, it, st_o, st_ml);
 }
 
 }  // namespace fairkv

@@ -16,26 +16,30 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
     // both the row-contiguous fill and the one-row-per-lane read are free of bank conflicts.
     __shared__ uint4 lds_k[kWaves][kTile * LPR];
     __shared__ float lds_p[kWaves][kTile][G];
+    __shared__ int flag;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-
-    const fairkv_item it = a.items[blockIdx.x];
-    const int b = it.b, h = it.h;
-    // an item that does not belong to this problem is skipped by the whole workgroup
-    if (b < 0 || b >= a.B || h < 0 || h >= a.Hkv || it.tok_begin < 0 || it.part < 0) return;
-    const int pair = b * a.Hkv + h;
-    const int64_t row0 = a.off[pair] + it.tok_begin;
-    int n = min(it.tok_count, a.len[pair] - it.tok_begin);   // never read past the pair's rows
-    n = max(n, 0);
-    const int n_tiles = (n + kTile - 1) / kTile;
-
-    const char *kbase = static_cast<const char *>(a.k) + row0 * ROW_BYTES;
-    const char *vbase = static_cast<const char *>(a.v) + row0 * ROW_BYTES;
-    const uint32_t *qrow = static_cast<const uint32_t *>(a.q) + static_cast<size_t>(b * a.Hq + h * G) * DW;
-
     const int my_piece = lane % LPR;   // which 16 bytes of a row this lane moves / accumulates
     const int my_sub = lane / LPR;     // which of the RPI rows of a wave-wide access
+    float *st_o = reinterpret_cast<float *>(&lds_k[0][0]);   // [kWaves][G][D], reuses the K tiles
+    float *st_ml = st_o + kWaves * G * D;                    // [kWaves][G][2]
+    static_assert(sizeof(float) * (kWaves * G * (D + 2)) <= sizeof(uint4) * kWaves * kTile * LPR,
+                  "merge staging must fit in the K tiles");
+
+    // persistent workgroup: walk the items the planner gave this slot
+    const int i_begin = a.slot_ptr[blockIdx.x], i_end = a.slot_ptr[blockIdx.x + 1];
+    for (int ii = i_begin; ii < i_end; ++ii) {
+    const fairkv_item it = a.items[ii];
+    const int b = it.b, h = it.h;
+    // an item that does not belong to this problem is skipped by the whole workgroup
+    if (b < 0 || b >= a.B || h < 0 || h >= a.Hkv || it.row < 0 || it.part < 0 || it.part >= a.n_parts) continue;
+    const int n = max(it.tok_count, 0);
+    const int n_tiles = (n + kTile - 1) / kTile;
+
+    const char *kbase = static_cast<const char *>(a.k) + it.row * ROW_BYTES;
+    const char *vbase = static_cast<const char *>(a.v) + it.row * ROW_BYTES;
+    const uint32_t *qrow = static_cast<const uint32_t *>(a.q) + static_cast<size_t>(b * a.Hq + h * G) * DW;
 
     float o[G][EPC];
     float m_run[G], l_lane[G];
@@ -154,10 +158,6 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
     }
 
     __syncthreads();   // every wave is done with its K tile: reuse that memory
-    float *st_o = reinterpret_cast<float *>(&lds_k[0][0]);   // [kWaves][G][D]
-    float *st_ml = st_o + kWaves * G * D;                    // [kWaves][G][2]
-    static_assert(sizeof(float) * (kWaves * G * (D + 2)) <= sizeof(uint4) * kWaves * kTile * LPR,
-                  "merge staging must fit in the K tiles");
     if (my_sub == 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
@@ -171,9 +171,8 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
             st_ml[(wave * G + g) * 2 + 1] = l_lane[g];
         }
     }
-    __syncthreads();
-
-    workgroup_epilogue<D, G>(a, it, st_o, st_ml);
+    item_epilogue<D, G>(a, it, st_o, st_ml, &flag);
+    }   // items of the slot
 }
 
 }  // namespace fairkv

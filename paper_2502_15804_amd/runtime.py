@@ -9,8 +9,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (FAIRKV_POLICY_LPT_SPLIT, Plan, fairkv_decode_attn, fairkv_default_params, fairkv_plan,
-               fairkv_workspace_bytes)
+from . import Plan, fairkv_decode_attn, fairkv_default_params, fairkv_plan, fairkv_workspace_bytes
 
 
 def device_compute_units(device=None) -> int:
@@ -35,18 +34,14 @@ class DecodeLayer:
         self.G = self.Hq // self.Hkv
         self.scale = float(scale)
         if params is None:
-            params = fairkv_default_params(device_compute_units(dev), policy=FAIRKV_POLICY_LPT_SPLIT)
-        self.plan: Plan = fairkv_plan(lens_h, self.B, self.Hkv, params)
-        self.lens_d = torch.from_numpy(lens_h).to(dev)
-        self.off_d = torch.from_numpy(off_h).to(dev)
-        items_bytes = self.plan.items.view(np.uint8) if self.plan.n_items else np.zeros(32, np.uint8)
-        self.items_d = torch.from_numpy(items_bytes.copy()).to(dev)
-        if not self.plan.n_items:
-            self.items_d = self.items_d[:0]
+            params = fairkv_default_params(device_compute_units(dev))
+        self.plan: Plan = fairkv_plan(lens_h, off_h, self.B, self.Hkv, params)
+        self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
+        self.slot_ptr_d = torch.from_numpy(self.plan.slot_ptr).to(dev)
         self.part_base_d = torch.from_numpy(self.plan.part_base).to(dev)
-        need = fairkv_workspace_bytes(self.plan.n_parts, self.G, self.D)
+        need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G, self.D)
         if workspace is None:
-            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+            workspace = torch.zeros(need, dtype=torch.uint8, device=dev)   # arrival counters start at zero
         elif workspace.numel() < need:
             raise ValueError("shared workspace too small for this layer")
         self.workspace = workspace
@@ -54,6 +49,6 @@ class DecodeLayer:
         self.lse = torch.empty((self.B, self.Hq), dtype=torch.float32, device=dev) if want_lse else None
 
     def run(self, stream=None):
-        fairkv_decode_attn(self.q, self.k, self.v, self.off_d, self.lens_d, self.items_d, self.part_base_d,
-                           self.plan.n_parts, self.workspace, self.out, self.lse, self.scale, stream)
+        fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.slot_ptr_d, self.part_base_d,
+                           self.plan.n_parts, self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
         return self.out, self.lse

@@ -41,14 +41,20 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(F.fairkv_plan_summary) == 32
     p = F.fairkv_default_params(256)
     assert (p.n_slots, p.tile, p.min_chunk, p.max_split, p.oversub, p.overhead_tokens, p.policy) == \
-        (512, 64, 256, 128, 2, 64, F.FAIRKV_POLICY_LPT_SPLIT)
+        (256, 16, 64, 256, 2, 32, F.FAIRKV_POLICY_FAIR)
+    d = OP.Params()
+    assert (d.n_slots, d.tile, d.min_chunk, d.max_split, d.oversub, d.overhead_tokens, d.policy) == \
+        (256, 16, 64, 256, 2, 32, OP.POLICY_FAIR)
 
 
-def _same_as_oracle(lens, B, Hkv, **kw):
+def _same_as_oracle(lens, B, Hkv, offs=None, **kw):
+    lens = np.asarray(lens).reshape(B, Hkv)
+    if offs is None:
+        offs = W.packed_offsets(lens, gap_rows=1)[0]
     op = OP.Params(**kw)
-    o_items, o_slot_ptr, _, o_part_base, o_sum = OP.plan(np.asarray(lens).reshape(-1), B, Hkv, op)
+    o_items, o_slot_ptr, o_part_base, o_sum = OP.plan(lens.reshape(-1), np.asarray(offs).reshape(-1), B, Hkv, op)
     p = F.fairkv_default_params(1, **kw)
-    plan = F.fairkv_plan(lens, B, Hkv, p)
+    plan = F.fairkv_plan(lens, offs, B, Hkv, p)
     got = [tuple(int(x) for x in rec) for rec in plan.items.tolist()]
     assert got == [it.astuple() for it in o_items]
     assert plan.slot_ptr.tolist() == o_slot_ptr
@@ -56,60 +62,64 @@ def _same_as_oracle(lens, B, Hkv, **kw):
     s = plan.summary
     assert (s.total_tokens, s.max_slot_load, s.min_slot_load, s.n_items, s.n_parts) == \
         (o_sum.total_tokens, o_sum.max_slot_load, o_sum.min_slot_load, o_sum.n_items, o_sum.n_parts)
+    assert plan.slot_loads().max() == o_sum.max_slot_load
 
 
 @pytest.mark.parametrize("name", list(W.WORKLOADS))
-@pytest.mark.parametrize("policy", [0, 1, 2])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
 def test_plan_is_bit_exact_on_the_workloads(name, policy):
     w = W.WORKLOADS[name]
     for layer in range(2):
-        _same_as_oracle(W.lens(name, layer=layer), w.B, w.Hkv, n_slots=512, policy=policy)
+        _same_as_oracle(W.lens(name, layer=layer), w.B, w.Hkv, n_slots=256, policy=policy)
 
 
 def test_plan_is_bit_exact_on_random_cases():
     rng = np.random.default_rng(42)
-    for _ in range(1000):
+    for _ in range(1200):
         B, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 9))
         lens = rng.integers(0, 5001, size=(B, Hkv)).astype(np.int32)
         lens[rng.random((B, Hkv)) < 0.1] = 0
         if rng.random() < 0.2:
             lens = (lens // 512) * 512          # many exact ties
-        tile = int(rng.choice([1, 8, 64, 128]))
+        tile = int(rng.choice([1, 8, 16, 64, 128]))
         _same_as_oracle(lens, B, Hkv, n_slots=int(rng.integers(1, 65)), tile=tile,
                         min_chunk=tile * int(rng.integers(1, 9)), max_split=int(rng.integers(1, 40)),
                         oversub=int(rng.integers(1, 5)), overhead_tokens=int(rng.integers(0, 200)),
-                        policy=int(rng.integers(0, 3)))
+                        policy=int(rng.integers(0, 4)))
 
 
 def test_plan_sizing_call_and_capacity_error():
     lens = np.array([[1000, 0], [300, 4000]], np.int32)
+    off = np.array([[0, 1000], [1000, 1300]], np.int64)
     p = F.fairkv_default_params(4)
     s = F.fairkv_plan_summary()
     L = F.lib()
-    rc = L.fairkv_plan(lens.ctypes.data, 2, 2, ctypes.byref(p), None, 0, None, None, ctypes.byref(s))
-    assert rc == F.FAIRKV_ECAP and s.n_items > 3 and s.total_tokens == 5300
+    rc = L.fairkv_plan(lens.ctypes.data, off.ctypes.data, 2, 2, ctypes.byref(p), None, 0, None, None, ctypes.byref(s))
+    assert rc == F.FAIRKV_ECAP and s.n_items > 4 and s.total_tokens == 5300
     items = np.zeros(s.n_items, dtype=F.ITEM_DTYPE)
     small = np.full(2, -7, dtype=F.ITEM_DTYPE)
-    rc = L.fairkv_plan(lens.ctypes.data, 2, 2, ctypes.byref(p), small.ctypes.data, 2, None, None, ctypes.byref(s))
-    assert rc == F.FAIRKV_ECAP and (small["b"] == -7).all()          # nothing written
-    rc = L.fairkv_plan(lens.ctypes.data, 2, 2, ctypes.byref(p), items.ctypes.data, items.size, None, None,
+    rc = L.fairkv_plan(lens.ctypes.data, off.ctypes.data, 2, 2, ctypes.byref(p), small.ctypes.data, 2, None, None,
                        ctypes.byref(s))
+    assert rc == F.FAIRKV_ECAP and (small["b"] == -7).all()          # nothing written
+    rc = L.fairkv_plan(lens.ctypes.data, off.ctypes.data, 2, 2, ctypes.byref(p), items.ctypes.data, items.size,
+                       None, None, ctypes.byref(s))
     assert rc == F.FAIRKV_OK and int(items["tok_count"].sum()) == 5300
 
 
 def test_plan_all_empty_pairs():
-    plan = F.fairkv_plan(np.zeros((3, 2), np.int32), 3, 2, F.fairkv_default_params(8))
-    assert plan.n_items == 0 and plan.n_parts == 0 and plan.part_base.tolist() == [0] * 7
-    assert plan.summary.max_slot_load == 0
+    plan = F.fairkv_plan(np.zeros((3, 2), np.int32), np.zeros((3, 2), np.int64), 3, 2, F.fairkv_default_params(8))
+    # every empty pair gets one empty item, so that its zero output is written by somebody
+    assert plan.n_items == 6 and plan.n_parts == 6 and plan.part_base.tolist() == list(range(7))
+    assert (plan.items["tok_count"] == 0).all() and plan.summary.total_tokens == 0
 
 
 @pytest.mark.parametrize("bad", [dict(n_slots=0), dict(tile=0), dict(min_chunk=100), dict(max_split=0),
-                                 dict(oversub=0), dict(overhead_tokens=-1), dict(policy=3), dict(reserved=1),
+                                 dict(oversub=0), dict(overhead_tokens=-1), dict(policy=4), dict(reserved=1),
                                  dict(min_chunk=0)])
 def test_plan_rejects_bad_parameters(bad):
     p = F.fairkv_default_params(4, **bad)
     with pytest.raises(F.FairKVError) as e:
-        F.fairkv_plan(np.ones((1, 1), np.int32), 1, 1, p)
+        F.fairkv_plan(np.ones((1, 1), np.int32), np.zeros((1, 1), np.int64), 1, 1, p)
     assert e.value.code == F.FAIRKV_EINVAL
 
 
@@ -117,21 +127,28 @@ def test_plan_rejects_bad_inputs():
     L = F.lib()
     p = F.fairkv_default_params(4)
     s = F.fairkv_plan_summary()
-    lens = np.array([5, -1], np.int32)
-    assert L.fairkv_plan(lens.ctypes.data, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
-    assert L.fairkv_plan(None, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
-    assert L.fairkv_plan(lens.ctypes.data, 0, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
-    assert L.fairkv_plan(lens.ctypes.data, 2, 1, ctypes.byref(p), None, 4, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
-    assert L.fairkv_plan(lens.ctypes.data, 2, 1, ctypes.byref(p), None, 0, None, None, None) == F.FAIRKV_EINVAL
+    bad = np.array([5, -1], np.int32)
+    good = np.array([5, 1], np.int32)
+    off = np.array([0, 5], np.int64)
+    neg = np.array([0, -5], np.int64)
+    lp, op = good.ctypes.data, off.ctypes.data
+    assert L.fairkv_plan(bad.ctypes.data, op, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, neg.ctypes.data, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(None, op, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, None, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, op, 0, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, op, 2, 1, ctypes.byref(p), None, 4, None, None, ctypes.byref(s)) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, op, 2, 1, ctypes.byref(p), None, 0, None, None, None) == F.FAIRKV_EINVAL
+    assert L.fairkv_plan(lp, op, 2, 1, ctypes.byref(p), None, 0, None, None, ctypes.byref(s)) == F.FAIRKV_ECAP
     with pytest.raises(F.FairKVError):
         F.fairkv_default_params(0)
 
 
 def test_workspace_bytes():
-    assert F.fairkv_workspace_bytes(0, 8, 128) >= 0
-    need = F.fairkv_workspace_bytes(10, 8, 128)
-    assert need >= 10 * 8 * 130 * 4 and need % 256 == 0
-    assert F.fairkv_workspace_bytes(-1, 8, 128) == 0 and F.fairkv_workspace_bytes(1, 0, 128) == 0
+    need = F.fairkv_workspace_bytes(10, 6, 8, 128)
+    assert need >= 10 * 8 * 130 * 4 + 6 * 4 and need % 256 == 0
+    assert F.fairkv_workspace_bytes(-1, 6, 8, 128) == 0 and F.fairkv_workspace_bytes(1, 6, 0, 128) == 0
+    assert F.fairkv_workspace_bytes(1, 0, 8, 128) == 0
 
 
 def test_decode_attn_validates_before_any_launch():
@@ -140,15 +157,18 @@ def test_decode_attn_validates_before_any_launch():
     L = F.lib()
     fake = ctypes.c_void_p(0x1000)
 
-    def call(q=fake, k=fake, v=fake, off=fake, ln=fake, items=fake, n_items=1, pb=fake, n_parts=1, ws=fake,
+    def call(q=fake, k=fake, v=fake, items=fake, n_items=1, sp=fake, n_slots=1, pb=fake, n_parts=1, ws=fake,
              ws_bytes=1 << 30, out=fake, lse=None, B=1, Hq=8, Hkv=1, D=128, idt=0, odt=1, scale=0.1):
-        return L.fairkv_decode_attn(q, k, v, off, ln, items, n_items, pb, n_parts, ws, ws_bytes, out, lse,
+        return L.fairkv_decode_attn(q, k, v, items, n_items, sp, n_slots, pb, n_parts, ws, ws_bytes, out, lse,
                                     B, Hq, Hkv, D, idt, odt, scale, None)
 
     assert call(q=None) == F.FAIRKV_EINVAL
     assert call(out=None) == F.FAIRKV_EINVAL
     assert call(items=None) == F.FAIRKV_EINVAL
+    assert call(sp=None) == F.FAIRKV_EINVAL
     assert call(B=0) == F.FAIRKV_EINVAL
+    assert call(n_slots=0) == F.FAIRKV_EINVAL
+    assert call(n_items=0) == F.FAIRKV_EINVAL                      # every pair has at least one item
     assert call(Hq=7, Hkv=2) == F.FAIRKV_EINVAL
     assert call(n_parts=0) == F.FAIRKV_EINVAL                      # fewer parts than items
     assert call(scale=float("nan")) == F.FAIRKV_EINVAL

@@ -24,17 +24,19 @@ def make_case(B, Hq, Hkv, D, dtype, lens, seed, gap_rows=0):
     return w, off, q, k, v
 
 
-def run_hip(w, q, k, v, off, lens, policy=2, n_slots=512, out_dtype=None, poison=True, **params):
+def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison=True, calls=1, **params):
     from paper_2502_15804_amd.runtime import DecodeLayer
     F = _F()
     p = F.fairkv_default_params(256, policy=policy, n_slots=n_slots, **params)
     layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype)
-    if poison:
-        layer.out.fill_(float("nan"))
-        layer.lse.fill_(float("nan"))
-        layer.workspace.fill_(0xFF)
-    layer.run()
-    torch.cuda.synchronize()
+    for _ in range(calls):      # a second call checks that the first left the arrival counters at zero
+        if poison:
+            layer.out.fill_(float("nan"))
+            layer.lse.fill_(float("nan"))
+            counters = -(-lens.size * 4 // 256) * 256          # the last region of the workspace
+            layer.workspace[: layer.workspace.numel() - counters].fill_(0xFF)
+        layer.run()
+        torch.cuda.synchronize()
     return layer.out.float().cpu().numpy().astype(np.float64), layer.lse.cpu().numpy().astype(np.float64), layer
 
 
@@ -58,11 +60,13 @@ def test_tiny_workload_fp32():
     lens = W.lens("tiny", seed=0)
     off, total = W.packed_offsets(lens)
     q, k, v = W.make_qkv(w, total, seed=0)
-    for policy in (0, 1, 2):
+    for policy in (0, 1, 2, 3):
         check(w, q, k, v, off, lens, policy=policy)
     # force splitting even of these short heads: chunks of 16 tokens
-    err, layer = check(w, q, k, v, off, lens, policy=2, tile=16, min_chunk=16, n_slots=64, oversub=1)
-    assert layer.plan.n_items > 8
+    for policy in (2, 3):
+        err, layer = check(w, q, k, v, off, lens, policy=policy, tile=16, min_chunk=16, n_slots=64, oversub=1,
+                           overhead_tokens=0, calls=2)
+        assert layer.plan.n_items > 8
 
 
 @pytest.mark.parametrize("dtype,D,G", [("bf16", 128, 8), ("bf16", 128, 4), ("bf16", 128, 2), ("bf16", 128, 1),
@@ -77,8 +81,8 @@ def test_shapes_with_ragged_tails_and_chunks(dtype, D, G):
     lens[2, 0] = 64 * 7       # whole tiles exactly
     lens[2, 1] = 64 * 5 + 1   # one token into a new tile
     w, off, q, k, v = make_case(B, Hkv * G, Hkv, D, dtype, lens, seed=G, gap_rows=3)
-    for policy in (0, 2):
-        check(w, q, k, v, off, lens, policy=policy, n_slots=16, oversub=2, min_chunk=128)
+    for policy, n_slots in ((0, 16), (2, 16), (3, 16), (3, 3), (1, 300)):
+        check(w, q, k, v, off, lens, policy=policy, n_slots=n_slots, oversub=2, min_chunk=64, calls=2)
 
 
 def test_chunked_equals_unchunked_on_the_gpu():
@@ -89,7 +93,7 @@ def test_chunked_equals_unchunked_on_the_gpu():
     lens = rng.integers(200, 3000, size=(2, 2)).astype(np.int32)
     w, off, q, k, v = make_case(2, 16, 2, 128, "bf16", lens, seed=5)
     o1, l1, _ = run_hip(w, q, k, v, off, lens, policy=0)
-    o2, l2, layer = run_hip(w, q, k, v, off, lens, policy=2, n_slots=64, min_chunk=64, oversub=1)
+    o2, l2, layer = run_hip(w, q, k, v, off, lens, policy=3, n_slots=64, min_chunk=64, overhead_tokens=0)
     assert layer.plan.n_items > 16
     assert np.abs(o1 - o2).max() < 2e-3 and np.abs(l1 - l2).max() < 2e-3
     ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
@@ -100,7 +104,7 @@ def test_all_heads_empty():
     lens = np.zeros((2, 2), np.int32)
     w, off, q, k, v = make_case(2, 8, 2, 128, "bf16", lens, seed=1)
     out, lse, layer = run_hip(w, q, k, v, off, lens)
-    assert layer.plan.n_items == 0 and (out == 0).all() and np.isneginf(lse).all()
+    assert layer.plan.n_items == 4 and (out == 0).all() and np.isneginf(lse).all()
 
 
 def test_length_one_returns_the_value_row_exactly():
@@ -117,7 +121,7 @@ def test_large_scores_do_not_overflow():
     lens = np.array([[300]], np.int32)
     w, off, q, k, v = make_case(1, 8, 1, 128, "f32", lens, seed=3)
     k = k * 8.0      # scores of order +-100
-    check(w, q, k, v, off, lens, tol=2e-5, policy=2, n_slots=4, min_chunk=64, oversub=1)
+    check(w, q, k, v, off, lens, tol=2e-5, policy=3, n_slots=4, min_chunk=64)
 
 
 def test_rows_outside_the_heads_are_never_read():
@@ -175,7 +179,7 @@ def test_full_size_workloads_every_output(name):
         assert err <= w.tol, f"{name} layer {layer_idx}: max abs err {err:.3e}"
         fin = np.isfinite(rl)
         assert np.array_equal(np.isneginf(lse), ~fin) and np.abs(lse[fin] - rl[fin]).max() <= w.tol
-        for policy in ((0,) if layer_idx == 0 else ()):
+        for policy in ((0, 2) if layer_idx == 0 else ()):
             p = _F().fairkv_default_params(256, policy=policy)
             naive = DecodeLayer(layer.q, layer.k, layer.v, off, lens, w.scale, params=p)
             naive.run()
