@@ -49,6 +49,7 @@ typedef enum {
 } fairkv_status;
 
 enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1 };
+enum { FAIRKV_MAX_SLOTS = 768 };   /* most slots a plan handed to fairkv_decode_attn may have */
 
 /* How the work list is built; the four mirror the paper's ablation (Section 5.2.1).
  *   NAIVE      pairs dealt to slots round-robin in (b, h) order, unsplit: the analogue of the
@@ -63,16 +64,17 @@ enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1 };
  *              Reaches the lower bound of eq. 4 up to min_chunk and the per-item overhead. */
 enum { FAIRKV_POLICY_NAIVE = 0, FAIRKV_POLICY_LPT = 1, FAIRKV_POLICY_LPT_SPLIT = 2, FAIRKV_POLICY_FAIR = 3 };
 
-/* One unit of work: tokens [tok_begin, tok_begin + tok_count) of pair (b, h), i.e. rows
- * row ... row + tok_count - 1 of K and V, for all G query heads of the group.  n_chunks is
- * the number of items the pair was cut into and part the index of this item's partial
- * result (part_base[pair] + chunk index).  A pair without tokens has one item with
- * tok_count == 0, so that some slot writes its zero output. */
+/* One unit of work: rows row ... row + tok_count - 1 of K and V, a chunk of pair (b, h),
+ * for all G query heads of the group.  The pair was cut into n_chunks items, of which this
+ * is number `chunk` (in token order: the first token of the chunk is row - off[b][h]);
+ * part is the index of this item's partial result, and the partials of a pair are
+ * consecutive: part - chunk ... part - chunk + n_chunks - 1.  A pair without tokens has
+ * one item with tok_count == 0, so that some slot writes its zero output. */
 typedef struct {
-    int64_t row;        /* off[b][h] + tok_begin */
+    int64_t row;
     int32_t tok_count;
     int32_t b, h;
-    int32_t tok_begin;
+    int32_t chunk;
     int32_t n_chunks;
     int32_t part;
 } fairkv_item;          /* 32 bytes */
@@ -97,8 +99,9 @@ typedef struct {
     int32_t n_parts;         /* partial-result slots the workspace must hold (== n_items) */
 } fairkv_plan_summary;
 
-/* Defaults: n_slots = n_compute_units, tile 16, min_chunk 64, max_split 256, oversub 2,
- * overhead_tokens 32, policy FAIR.  n_compute_units must be >= 1. */
+/* Defaults: n_slots = n_compute_units, tile 16, min_chunk 32, max_split 256, oversub 2,
+ * overhead_tokens 192 (measured on MI355X: an extra item in a slot costs about as much as
+ * streaming 200-300 tokens), policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
 /*
@@ -155,9 +158,12 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  *
  * q          device [B][Hq][D], element type in_dtype
  * k, v       device [n_rows][D], element type in_dtype, 16-byte aligned
- * items      device [n_items], slot_ptr device [n_slots+1], part_base device [B*Hkv+1]: a plan
- *            made by fairkv_plan from this cache's len and off, copied to the device by the
- *            caller.  The kernels read exactly the rows the items name.
+ * items      device [n_items]: the items of a plan made by fairkv_plan from this cache's len
+ *            and off, copied to the device by the caller.  The kernels read exactly the rows
+ *            the items name.
+ * slot_ptr   HOST [n_slots+1]: the plan's slot pointer.  It travels to the GPU inside the
+ *            kernel arguments (one memory round trip less before the first K/V row is
+ *            requested), which limits n_slots to FAIRKV_MAX_SLOTS.
  * workspace  device, at least fairkv_workspace_bytes(n_parts, B*Hkv, G, D) bytes, 16-byte
  *            aligned, zero-filled before its first use (see fairkv_workspace_bytes)
  * out        device [B][Hq][D], element type out_dtype (FAIRKV_F32, or FAIRKV_BF16 rounded
@@ -166,12 +172,13 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * scale      multiplies the scores (1/sqrt(D) in the usual models)
  * hip_stream a hipStream_t (NULL = the default stream)
  *
- * Supported: D in {64, 128}; in_dtype BF16 or F32; G = Hq/Hkv in {1, 2, 4, 8}.
+ * Supported: D in {64, 128}; in_dtype BF16 or F32; G = Hq/Hkv in {1, 2, 4, 8};
+ * n_slots <= FAIRKV_MAX_SLOTS (else FAIRKV_EUNSUPPORTED).
  * Calls that share a workspace must be ordered on one stream.
  */
 int fairkv_decode_attn(const void *q, const void *k, const void *v,
                        const fairkv_item *items, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
-                       const int32_t *part_base, int32_t n_parts, void *workspace, size_t workspace_bytes,
+                       int32_t n_parts, void *workspace, size_t workspace_bytes,
                        void *out, float *lse,
                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
                        int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream);

@@ -46,25 +46,25 @@ POLICY_FAIR = 3
 class Params:
     n_slots: int = 256
     tile: int = 16
-    min_chunk: int = 64
+    min_chunk: int = 32
     max_split: int = 256
     oversub: int = 2
-    overhead_tokens: int = 32
+    overhead_tokens: int = 192
     policy: int = POLICY_FAIR
 
 
 @dataclass(frozen=True)
 class Item:
-    row: int          # first K/V row: off[b][h] + tok_begin
+    row: int          # first K/V row: off[b][h] + first token of the chunk
     tok_count: int
     b: int
     h: int
-    tok_begin: int
+    chunk: int        # which piece of the pair, in token order
     n_chunks: int
-    part: int         # part_base[pair] + chunk index
+    part: int         # part_base[pair] + chunk
 
     def astuple(self) -> Tuple[int, ...]:
-        return (self.row, self.tok_count, self.b, self.h, self.tok_begin, self.n_chunks, self.part)
+        return (self.row, self.tok_count, self.b, self.h, self.chunk, self.n_chunks, self.part)
 
 
 @dataclass(frozen=True)
@@ -209,7 +209,7 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
     for j in range(S):
         for (pair, begin, count, c) in slots[j]:
             b, h = divmod(pair, Hkv)
-            items.append(Item(offs[pair] + begin, count, b, h, begin, n_chunks_of[pair], part_base[pair] + c))
+            items.append(Item(offs[pair] + begin, count, b, h, c, n_chunks_of[pair], part_base[pair] + c))
         slot_ptr[j + 1] = len(items)
         loads.append(sum(pc[2] + ov for pc in slots[j]))
 

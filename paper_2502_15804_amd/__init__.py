@@ -26,7 +26,7 @@ EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fa
 
 class fairkv_item(ctypes.Structure):
     _fields_ = [("row", ctypes.c_int64)] + [(n, ctypes.c_int32) for n in
-                                            ("tok_count", "b", "h", "tok_begin", "n_chunks", "part")]
+                                            ("tok_count", "b", "h", "chunk", "n_chunks", "part")]
 
 
 class fairkv_plan_params(ctypes.Structure):
@@ -69,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.fairkv_workspace_bytes.restype = ctypes.c_size_t
         L.fairkv_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.fairkv_decode_attn.restype = ctypes.c_int
-        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp,
+        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
                                          i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
@@ -157,13 +157,14 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def fairkv_decode_attn(q, k, v, items, slot_ptr, part_base, n_parts, workspace, out, lse, scale, Hkv, stream=None):
+def fairkv_decode_attn(q, k, v, items, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
 
-    All tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
-    items: uint8 view of the plan's item array (n_items * 32 bytes); slot_ptr int32 [n_slots+1];
-    part_base int32 [B*Hkv+1]; workspace uint8, zero-filled before its first use; out [B,Hq,D]
-    float32 or bfloat16; lse float32 [B,Hq] or None.  Nothing is allocated or synchronised here.
+    Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
+    items: uint8 view of the plan's item array (n_items * 32 bytes); workspace uint8, zero-filled
+    before its first use; out [B,Hq,D] float32 or bfloat16; lse float32 [B,Hq] or None.
+    slot_ptr is the plan's HOST array (numpy int32 [n_slots+1]).  Nothing is allocated or
+    synchronised here.
     """
     import torch
 
@@ -171,19 +172,17 @@ def fairkv_decode_attn(q, k, v, items, slot_ptr, part_base, n_parts, workspace, 
     dt = {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}
     if q.dtype not in dt or k.dtype != q.dtype or v.dtype != q.dtype or out.dtype not in dt:
         raise TypeError("q/k/v must share bf16 or fp32; out must be bf16 or fp32")
-    for name, t in (("q", q), ("k", k), ("v", v), ("items", items), ("slot_ptr", slot_ptr),
-                    ("part_base", part_base), ("workspace", workspace), ("out", out), ("lse", lse)):
+    for name, t in (("q", q), ("k", k), ("v", v), ("items", items), ("workspace", workspace), ("out", out),
+                    ("lse", lse)):
         if t is None:
             continue
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous device tensor")
-    if slot_ptr.dtype != torch.int32 or part_base.dtype != torch.int32:
-        raise TypeError("slot_ptr and part_base must be int32")
+    if not isinstance(slot_ptr, np.ndarray) or slot_ptr.dtype != np.int32 or not slot_ptr.flags.c_contiguous:
+        raise TypeError("slot_ptr must be a contiguous host int32 array")
     if lse is not None and lse.dtype != torch.float32:
         raise TypeError("lse must be float32")
-    if k.shape[1] != D or v.shape != k.shape:
-        raise ValueError("shape mismatch")
-    if part_base.numel() != B * Hkv + 1 or tuple(out.shape) != (B, Hq, D) or slot_ptr.numel() < 2:
+    if k.shape[1] != D or v.shape != k.shape or tuple(out.shape) != (B, Hq, D) or slot_ptr.size < 2:
         raise ValueError("shape mismatch")
     item_bytes = items.numel() * items.element_size()
     if item_bytes % 32 != 0:
@@ -191,8 +190,8 @@ def fairkv_decode_attn(q, k, v, items, slot_ptr, part_base, n_parts, workspace, 
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     rc = lib().fairkv_decode_attn(
-        _ptr(q), _ptr(k), _ptr(v), _ptr(items), item_bytes // 32, _ptr(slot_ptr), slot_ptr.numel() - 1,
-        _ptr(part_base), int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _ptr(q), _ptr(k), _ptr(v), _ptr(items), item_bytes // 32, slot_ptr.ctypes.data, slot_ptr.size - 1,
+        int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(out), _ptr(lse), B, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
         ctypes.c_void_p(stream.cuda_stream))
     if rc != FAIRKV_OK:

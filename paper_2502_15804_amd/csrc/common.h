@@ -68,8 +68,6 @@ __device__ __forceinline__ float fetch_f32(const float *p)
 struct DecodeArgs {
     const void *q, *k, *v;
     const fairkv_item *items;   // grouped by slot
-    const int32_t *slot_ptr;    // [n_slots + 1]
-    const int32_t *part_base;   // [B*Hkv + 1]
     float *part_o;              // [n_parts][G][D]   unnormalised outputs relative to the item's maximum
     float *part_ml;             // [n_parts][G][2]   (maximum in log2 units, sum of weights)
     int32_t *arrivals;          // [B*Hkv] items of a cut pair that have delivered their partial; 0 between calls
@@ -77,7 +75,9 @@ struct DecodeArgs {
     float *lse;
     int32_t B, Hq, Hkv, out_dtype, n_parts;
     float scale_log2;           // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
+    int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1]); rides in the kernel arguments
 };
+static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
 // Layout facts shared by the stages.  A row of K or V is LPR 16-byte pieces; one wave-wide
 // 16-byte-per-lane access covers RPI whole rows, so every global access is a run of
@@ -152,18 +152,57 @@ __device__ __forceinline__ void merge_pair(const DecodeArgs &a, int b, int h, in
     }
 }
 
+// Partial results of cut pairs that a workgroup has finished but not yet handed over.  They
+// wait in LDS until the slot's list is done (or the buffer is full) and are then published
+// together, so that the hand-over, which costs several memory round trips, happens once per
+// workgroup and not in the middle of the stream.
+constexpr int kPend = 3;
+
+template <int D, int G>
+struct PendingParts {
+    float o[kPend][G * D];
+    float ml[kPend][G * 2];
+    int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend], last[kPend];
+};
+
+// Hand over the pending partials: publish them, wait until the stores are acknowledged,
+// count the workgroup in for each pair, and merge every pair for which it turned out to be
+// the last one (putting that pair's counter back to zero).  Called by all threads.
+template <int D, int G>
+__device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<D, G> &pend, int &n_pend)
+{
+    __syncthreads();
+    for (int p = 0; p < n_pend; ++p) {
+        const size_t base = static_cast<size_t>(pend.part[p]) * G;
+        for (int idx = threadIdx.x; idx < G * D; idx += kThreads) publish_f32(a.part_o + base * D + idx, pend.o[p][idx]);
+        if (threadIdx.x < G * 2) publish_f32(a.part_ml + base * 2 + threadIdx.x, pend.ml[p][threadIdx.x]);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have reached the shared level ...
+    __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
+    if (threadIdx.x < n_pend)
+        pend.last[threadIdx.x] = __hip_atomic_fetch_add(a.arrivals + pend.pair[threadIdx.x], 1, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT) == pend.n_chunks[threadIdx.x] - 1;
+    __syncthreads();
+    for (int p = 0; p < n_pend; ++p) {
+        if (!pend.last[p]) continue;   // every partial of the pair was published before its workgroup counted in
+        const int pair = pend.pair[p], nc = pend.n_chunks[p], p0 = pend.first_part[p];
+        if (p0 >= 0 && p0 + nc <= a.n_parts) merge_pair<D, G>(a, pair / a.Hkv, pair % a.Hkv, p0, nc);
+        if (threadIdx.x == 0)   // ready for the next call on this workspace
+            __hip_atomic_store(a.arrivals + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    n_pend = 0;
+    __syncthreads();
+}
+
 // End of one item, called by all threads of the workgroup after every wave has put its
 // unnormalised output, running maximum (log2 units) and weight sum into st_o [kWaves][G][D]
 // and st_ml [kWaves][G][2] in LDS.  Folds the waves:
 //   m* = max_w m_w,  l* = sum_w l_w 2^(m_w - m*),  o* = sum_w o_w 2^(m_w - m*).
-// An item that is a whole pair writes out = o*/l* and lse.  An item of a cut pair publishes
-// its partial (m*, l*, o*), waits until the stores are acknowledged, and counts itself in; the
-// workgroup that finds itself last merges all partials of the pair and puts the counter back
-// to zero.
-// `flag` is one int in LDS.  Ends with a barrier, so st_o/st_ml may be reused at once.
+// An item that is a whole pair writes out = o*/l* and lse.  An item of a cut pair leaves its
+// partial (m*, l*, o*) in `pend`.  Ends with a barrier, so st_o/st_ml may be reused at once.
 template <int D, int G>
 __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
-                                              const float *st_ml, int *flag)
+                                              const float *st_ml, PendingParts<D, G> &pend, int &n_pend)
 {
     const int b = it.b, h = it.h;
     const bool whole_pair = it.n_chunks == 1;
@@ -188,28 +227,25 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
                 a.lse[b * a.Hq + h * G + g] =
                     l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         } else {
-            publish_f32(a.part_o + (static_cast<size_t>(it.part) * G + g) * D + d, acc);
+            pend.o[n_pend][idx] = acc;
             if (d == 0) {
-                publish_f32(a.part_ml + (static_cast<size_t>(it.part) * G + g) * 2 + 0, m_star);
-                publish_f32(a.part_ml + (static_cast<size_t>(it.part) * G + g) * 2 + 1, l_star);
+                pend.ml[n_pend][g * 2 + 0] = m_star;
+                pend.ml[n_pend][g * 2 + 1] = l_star;
             }
         }
     }
-    if (whole_pair) {
-        __syncthreads();
-        return;
-    }
-    const int pair = b * a.Hkv + h;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have reached the shared level ...
-    __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
-    if (threadIdx.x == 0)
-        *flag = __hip_atomic_fetch_add(a.arrivals + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == it.n_chunks - 1;
-    __syncthreads();
-    if (*flag) {   // every partial of the pair was published before its workgroup counted in
-        const int p0 = a.part_base[pair];
-        if (p0 >= 0 && p0 + it.n_chunks <= a.n_parts) merge_pair<D, G>(a, b, h, p0, it.n_chunks);
-        if (threadIdx.x == 0)   // ready for the next call on this workspace
-            __hip_atomic_store(a.arrivals + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!whole_pair) {
+        if (threadIdx.x == 0) {
+            pend.pair[n_pend] = b * a.Hkv + h;
+            pend.part[n_pend] = it.part;
+            pend.first_part[n_pend] = it.part - it.chunk;   // the partials of a pair are consecutive
+            pend.n_chunks[n_pend] = it.n_chunks;
+        }
+        ++n_pend;
+        if (n_pend == kPend) {
+            flush_pending<D, G>(a, pend, n_pend);
+            return;
+        }
     }
     __syncthreads();
 }

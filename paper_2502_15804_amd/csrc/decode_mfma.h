@@ -84,7 +84,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     __shared__ __attribute__((aligned(16))) float st_o[kWaves * G * D];
     __shared__ float st_ml[kWaves * G * 2];
     __shared__ __attribute__((aligned(16))) ItemRef table[kTable];
-    __shared__ int flag;
+    __shared__ PendingParts<D, G> pend;
+    int n_pend = 0;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: loop control is scalar
@@ -273,10 +274,11 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     st_ml[(wave * G + l16) * 2 + 1] = l_run;
                 }
             }
-            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G>(a, it, st_o, st_ml, &flag);
+            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G>(a, it, st_o, st_ml, pend, n_pend);
         }
         wait_vmcnt<0>();   // nothing of this batch may still be landing in the rings
     }
+    if (n_pend > 0) flush_pending<D, G>(a, pend, n_pend);
 }
 
 }  // namespace fairkv

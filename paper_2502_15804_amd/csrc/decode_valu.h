@@ -16,7 +16,8 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
     // both the row-contiguous fill and the one-row-per-lane read are free of bank conflicts.
     __shared__ uint4 lds_k[kWaves][kTile * LPR];
     __shared__ float lds_p[kWaves][kTile][G];
-    __shared__ int flag;
+    __shared__ PendingParts<D, G> pend;
+    int n_pend = 0;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -171,8 +172,9 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
             st_ml[(wave * G + g) * 2 + 1] = l_lane[g];
         }
     }
-    item_epilogue<D, G>(a, it, st_o, st_ml, &flag);
+    item_epilogue<D, G>(a, it, st_o, st_ml, pend, n_pend);
     }   // items of the slot
+    if (n_pend > 0) flush_pending<D, G>(a, pend, n_pend);
 }
 
 }  // namespace fairkv

@@ -82,15 +82,19 @@ extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32
 
 extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, const fairkv_item *items,
                                   int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
-                                  const int32_t *part_base, int32_t n_parts, void *workspace,
+                                  int32_t n_parts, void *workspace,
                                   size_t workspace_bytes, void *out, float *lse, int32_t B, int32_t Hq,
                                   int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
                                   void *hip_stream)
 {
-    if (!q || !k || !v || !items || !slot_ptr || !part_base || !out) return FAIRKV_EINVAL;
+    if (!q || !k || !v || !items || !slot_ptr || !out) return FAIRKV_EINVAL;
     if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0) return FAIRKV_EINVAL;
     if (Hq % Hkv != 0) return FAIRKV_EINVAL;
     if (n_parts < n_items) return FAIRKV_EINVAL;
+    if (n_slots > FAIRKV_MAX_SLOTS) return FAIRKV_EUNSUPPORTED;
+    if (slot_ptr[0] != 0 || slot_ptr[n_slots] != n_items) return FAIRKV_EINVAL;
+    for (int32_t j = 0; j < n_slots; ++j)
+        if (slot_ptr[j] > slot_ptr[j + 1]) return FAIRKV_EINVAL;
     if (!(scale == scale) || std::isinf(scale)) return FAIRKV_EINVAL;
     if (in_dtype != FAIRKV_BF16 && in_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
     if (out_dtype != FAIRKV_BF16 && out_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
@@ -110,8 +114,7 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     a.k = k;
     a.v = v;
     a.items = items;
-    a.slot_ptr = slot_ptr;
-    a.part_base = part_base;
+    for (int32_t j = 0; j <= n_slots; ++j) a.slot_ptr[j] = slot_ptr[j];
     a.part_o = reinterpret_cast<float *>(ws);
     ws += align256(static_cast<size_t>(n_parts) * G * D * sizeof(float));
     a.part_ml = reinterpret_cast<float *>(ws);

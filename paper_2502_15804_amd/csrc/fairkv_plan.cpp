@@ -92,10 +92,10 @@ extern "C" int fairkv_default_params(fairkv_plan_params *p, int32_t n_compute_un
     if (!p || n_compute_units < 1 || n_compute_units > (1 << 20)) return FAIRKV_EINVAL;
     p->n_slots = n_compute_units;
     p->tile = 16;
-    p->min_chunk = 64;
+    p->min_chunk = 32;
     p->max_split = 256;
     p->oversub = 2;
-    p->overhead_tokens = 32;
+    p->overhead_tokens = 192;
     p->policy = FAIRKV_POLICY_FAIR;
     p->reserved = 0;
     return FAIRKV_OK;
@@ -203,7 +203,7 @@ extern "C" int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, in
         it.tok_count = pc.count;
         it.b = pc.pair / Hkv;
         it.h = pc.pair % Hkv;
-        it.tok_begin = pc.begin;
+        it.chunk = pc.chunk;
         it.n_chunks = n_chunks[static_cast<size_t>(pc.pair)];
         it.part = static_cast<int32_t>(base[pc.pair] + pc.chunk);
     }

@@ -37,8 +37,6 @@ class DecodeLayer:
             params = fairkv_default_params(device_compute_units(dev))
         self.plan: Plan = fairkv_plan(lens_h, off_h, self.B, self.Hkv, params)
         self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
-        self.slot_ptr_d = torch.from_numpy(self.plan.slot_ptr).to(dev)
-        self.part_base_d = torch.from_numpy(self.plan.part_base).to(dev)
         need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G, self.D)
         if workspace is None:
             workspace = torch.zeros(need, dtype=torch.uint8, device=dev)   # arrival counters start at zero
@@ -49,6 +47,6 @@ class DecodeLayer:
         self.lse = torch.empty((self.B, self.Hq), dtype=torch.float32, device=dev) if want_lse else None
 
     def run(self, stream=None):
-        fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.slot_ptr_d, self.part_base_d,
-                           self.plan.n_parts, self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
+        fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.slot_ptr, self.plan.n_parts,
+                           self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
         return self.out, self.lse

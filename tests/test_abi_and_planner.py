@@ -41,10 +41,10 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(F.fairkv_plan_summary) == 32
     p = F.fairkv_default_params(256)
     assert (p.n_slots, p.tile, p.min_chunk, p.max_split, p.oversub, p.overhead_tokens, p.policy) == \
-        (256, 16, 64, 256, 2, 32, F.FAIRKV_POLICY_FAIR)
+        (256, 16, 32, 256, 2, 192, F.FAIRKV_POLICY_FAIR)
     d = OP.Params()
     assert (d.n_slots, d.tile, d.min_chunk, d.max_split, d.oversub, d.overhead_tokens, d.policy) == \
-        (256, 16, 64, 256, 2, 32, OP.POLICY_FAIR)
+        (256, 16, 32, 256, 2, 192, OP.POLICY_FAIR)
 
 
 def _same_as_oracle(lens, B, Hkv, offs=None, **kw):
@@ -157,9 +157,12 @@ def test_decode_attn_validates_before_any_launch():
     L = F.lib()
     fake = ctypes.c_void_p(0x1000)
 
-    def call(q=fake, k=fake, v=fake, items=fake, n_items=1, sp=fake, n_slots=1, pb=fake, n_parts=1, ws=fake,
+    good_sp = np.array([0, 1], np.int32)
+
+    def call(q=fake, k=fake, v=fake, items=fake, n_items=1, sp=good_sp, n_slots=1, n_parts=1, ws=fake,
              ws_bytes=1 << 30, out=fake, lse=None, B=1, Hq=8, Hkv=1, D=128, idt=0, odt=1, scale=0.1):
-        return L.fairkv_decode_attn(q, k, v, items, n_items, sp, n_slots, pb, n_parts, ws, ws_bytes, out, lse,
+        spp = sp.ctypes.data if sp is not None else None
+        return L.fairkv_decode_attn(q, k, v, items, n_items, spp, n_slots, n_parts, ws, ws_bytes, out, lse,
                                     B, Hq, Hkv, D, idt, odt, scale, None)
 
     assert call(q=None) == F.FAIRKV_EINVAL
@@ -168,6 +171,10 @@ def test_decode_attn_validates_before_any_launch():
     assert call(sp=None) == F.FAIRKV_EINVAL
     assert call(B=0) == F.FAIRKV_EINVAL
     assert call(n_slots=0) == F.FAIRKV_EINVAL
+    assert call(sp=np.array([0, 2], np.int32)) == F.FAIRKV_EINVAL   # slot pointer does not end at n_items
+    assert call(sp=np.array([1, 1], np.int32)) == F.FAIRKV_EINVAL
+    big = np.zeros(2000, np.int32); big[-1] = 1
+    assert call(sp=big, n_slots=1999) == F.FAIRKV_EUNSUPPORTED      # too many slots for the kernel arguments
     assert call(n_items=0) == F.FAIRKV_EINVAL                      # every pair has at least one item
     assert call(Hq=7, Hkv=2) == F.FAIRKV_EINVAL
     assert call(n_parts=0) == F.FAIRKV_EINVAL                      # fewer parts than items

@@ -40,9 +40,9 @@ def check_invariants(lens, B, Hkv, p, offs, items, slot_ptr, part_base, s):
         cap = {P.POLICY_NAIVE: 1, P.POLICY_LPT: 1}.get(p.policy, p.max_split)
         assert 1 <= len(its) <= cap
         pos = 0
-        for x in its:
-            assert x.tok_begin == pos and x.tok_count > 0 and x.row == offs[pair] + pos
-            assert x.tok_begin % p.tile == 0            # cuts fall on tile boundaries of the pair
+        for c, x in enumerate(its):
+            assert x.chunk == c and x.tok_count > 0 and x.row == offs[pair] + pos
+            assert pos % p.tile == 0                    # cuts fall on tile boundaries of the pair
             pos += x.tok_count
         assert pos == n
         if p.policy == P.POLICY_LPT_SPLIT and len(its) > 1:
@@ -129,7 +129,7 @@ def test_split_ragged_tail_and_tile_rounding():
     # 1000 tokens, target 256 -> r = 4, cs = up(250) = 256, chunks 256,256,256,232
     p, offs, items, *_ = run([1000], 1, 1, n_slots=4, min_chunk=256, **kw)
     by_chunk = sorted(items, key=lambda x: x.part)
-    assert [(x.tok_begin, x.tok_count) for x in by_chunk] == [(0, 256), (256, 256), (512, 256), (768, 232)]
+    assert [(x.row - offs[0], x.tok_count) for x in by_chunk] == [(0, 256), (256, 256), (512, 256), (768, 232)]
     # 130 tokens, target 64 -> r = 3, cs = up(44) = 64 -> 64, 64, 2
     p, offs, items, *_ = run([130], 1, 1, n_slots=100, min_chunk=64, **kw)
     assert sorted(x.tok_count for x in items) == [2, 64, 64]
@@ -144,7 +144,7 @@ def test_fair_cut_by_hand():
     p, offs, items, slot_ptr, part_base, s = run([100, 300], 2, 1, offs=[0, 1000], n_slots=2, tile=16, min_chunk=32,
                                                  overhead_tokens=0, policy=P.POLICY_FAIR)
     assert [it.astuple() for it in items] == [(0, 100, 0, 0, 0, 1, 0), (1000, 96, 1, 0, 0, 2, 1),
-                                              (1096, 204, 1, 0, 96, 2, 2)]
+                                              (1096, 204, 1, 0, 1, 2, 2)]
     assert slot_ptr == [0, 2, 3] and part_base == [0, 1, 3]
     assert (s.max_slot_load, s.min_slot_load) == (204, 196)
     # room for 48 of the next 70 tokens: the rest (22) would be below min_chunk, and the excess is
