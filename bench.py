@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the policy comparison and the CPU baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run three plain device-to-device copies of this size and exit: a kernel of "
+                         "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     for name in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens"):
         ap.add_argument("--" + name.replace("_", "-"), type=int, default=None)
     return ap.parse_args()
@@ -123,6 +126,19 @@ def timed(rot, steps, warmup, use_graph):
     return t1 - t0, e0.elapsed_time(e1) * 1e-3, moved
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload, or None.
+    (Counters cannot be read from inside the timed run; the summary names the commands that made it.)"""
+    path = os.path.join(ROOT, "profiles", f"fairkv_decode_mfma_kernel_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(rot, seconds):
     """The fp64 oracle, as it stands, on the host cores: whole layers of the same workload."""
     import workloads as W
@@ -156,6 +172,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs the GPU", file=sys.stderr)
         sys.exit(2)
+    if a.copy_calibration:
+        n = a.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": n, "copies": 3}))
+        return
     F.lib()
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers
@@ -185,7 +211,7 @@ def main():
         "plan_host_us_per_layer": round(rot.plan_us, 1),
         "plan_layer0": {"max_slot_load": loads_max, "min_slot_load": loads_min, "efficiency_E": round(eff0, 4)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(a.workload),
                      "kernel": "fairkv_decode_mfma_kernel<128, 8>",
                      "bytes_per_launch": round(moved / a.steps), "us_per_launch": round(1e3 * ms_step, 3)},
         "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
