@@ -182,6 +182,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": n, "copies": 3}))
         return
+    if os.environ.get("FAIRKV_LIB"):        # A/B runs against another build of the library
+        F.LIB_PATH = os.environ["FAIRKV_LIB"]
     F.lib()
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers

@@ -49,7 +49,7 @@ typedef enum {
 } fairkv_status;
 
 enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1 };
-enum { FAIRKV_MAX_SLOTS = 768 };   /* most slots a plan handed to fairkv_decode_attn may have */
+enum { FAIRKV_MAX_SLOTS = 320 };   /* most slots a plan handed to fairkv_decode_attn may have */
 
 /* How the work list is built; the four mirror the paper's ablation (Section 5.2.1).
  *   NAIVE      pairs dealt to slots round-robin in (b, h) order, unsplit: the analogue of the
@@ -161,9 +161,13 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * items      device [n_items]: the items of a plan made by fairkv_plan from this cache's len
  *            and off, copied to the device by the caller.  The kernels read exactly the rows
  *            the items name.
- * slot_ptr   HOST [n_slots+1]: the plan's slot pointer.  It travels to the GPU inside the
- *            kernel arguments (one memory round trip less before the first K/V row is
- *            requested), which limits n_slots to FAIRKV_MAX_SLOTS.
+ * items_host HOST [n_items]: the same array as the planner wrote it, and
+ * slot_ptr   HOST [n_slots+1]: the plan's slot pointer.  The slot pointer and the first item
+ *            of every slot travel to the GPU inside the kernel arguments, so that a workgroup
+ *            requests its first K/V rows without first fetching its item list (two memory
+ *            round trips less at the start of a 20 us kernel); this limits n_slots to
+ *            FAIRKV_MAX_SLOTS.  items_host is also checked: every item must name a pair of
+ *            this problem, rows >= 0 and a partial slot below n_parts (else FAIRKV_EINVAL).
  * workspace  device, at least fairkv_workspace_bytes(n_parts, B*Hkv, G, D) bytes, 16-byte
  *            aligned, zero-filled before its first use (see fairkv_workspace_bytes)
  * out        device [B][Hq][D], element type out_dtype (FAIRKV_F32, or FAIRKV_BF16 rounded
@@ -177,7 +181,8 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * Calls that share a workspace must be ordered on one stream.
  */
 int fairkv_decode_attn(const void *q, const void *k, const void *v,
-                       const fairkv_item *items, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                       const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                       const int32_t *slot_ptr, int32_t n_slots,
                        int32_t n_parts, void *workspace, size_t workspace_bytes,
                        void *out, float *lse,
                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D,

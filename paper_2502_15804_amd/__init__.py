@@ -69,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.fairkv_workspace_bytes.restype = ctypes.c_size_t
         L.fairkv_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.fairkv_decode_attn.restype = ctypes.c_int
-        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
+        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
                                          i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
@@ -157,14 +157,14 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def fairkv_decode_attn(q, k, v, items, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None):
+def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
 
     Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
     items: uint8 view of the plan's item array (n_items * 32 bytes); workspace uint8, zero-filled
     before its first use; out [B,Hq,D] float32 or bfloat16; lse float32 [B,Hq] or None.
-    slot_ptr is the plan's HOST array (numpy int32 [n_slots+1]).  Nothing is allocated or
-    synchronised here.
+    items_host and slot_ptr are the plan's HOST arrays (numpy: fairkv_item records, int32
+    [n_slots+1]).  Nothing is allocated or synchronised here.
     """
     import torch
 
@@ -187,10 +187,14 @@ def fairkv_decode_attn(q, k, v, items, slot_ptr, n_parts, workspace, out, lse, s
     item_bytes = items.numel() * items.element_size()
     if item_bytes % 32 != 0:
         raise ValueError("items must be a whole number of 32-byte records")
+    if (not isinstance(items_host, np.ndarray) or items_host.dtype != ITEM_DTYPE or not items_host.flags.c_contiguous
+            or items_host.size * 32 != item_bytes):
+        raise TypeError("items_host must be the plan's contiguous item array, as many records as `items`")
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     rc = lib().fairkv_decode_attn(
-        _ptr(q), _ptr(k), _ptr(v), _ptr(items), item_bytes // 32, slot_ptr.ctypes.data, slot_ptr.size - 1,
+        _ptr(q), _ptr(k), _ptr(v), _ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data,
+        slot_ptr.size - 1,
         int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(out), _ptr(lse), B, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
         ctypes.c_void_p(stream.cuda_stream))

@@ -75,7 +75,10 @@ struct DecodeArgs {
     float *lse;
     int32_t B, Hq, Hkv, out_dtype, n_parts;
     float scale_log2;           // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
-    int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1]); rides in the kernel arguments
+    // What a workgroup needs before it has read anything from memory, riding in the kernel arguments:
+    int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1])
+    uint32_t first_row[FAIRKV_MAX_SLOTS];     // first K/V row of slot j's first item ...
+    uint32_t first_n[FAIRKV_MAX_SLOTS];       // ... and its token count; 0 = no early start for this slot
 };
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
@@ -94,62 +97,13 @@ struct Geo {
 };
 
 
-constexpr int kMergeBatch = 8;   // partials of a cut pair fetched at once by the merging workgroup
+constexpr int kMergeBatch = 4;   // partials of a cut pair fetched at once by the merging workgroup
 
-// Combine the n_chunks partials of a pair (the log-sum-exp merge):
-//   m* = max_c m_c,  l* = sum_c l_c 2^(m_c - m*),  out = sum_c o_c 2^(m_c - m*) / l*.
-// Exact in real arithmetic, so a cut pair gives what the whole pair would.  Called by all
-// threads of one workgroup; a thread owns four consecutive coordinates of one query head and
-// fetches up to kMergeBatch partials at once so that their latencies overlap.
-template <int D, int G>
-__device__ __forceinline__ void merge_pair(const DecodeArgs &a, int b, int h, int p0, int nc)
+// Two floats fetched as one 8-byte agent-scope load (see publish_f32 / fetch_f32 above).
+__device__ __forceinline__ float2 fetch_f32x2(const float *p)
 {
-    constexpr int D4 = D / 4;
-    for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
-        const int g = idx / D4, d = (idx % D4) * 4;
-        float m_star = -INFINITY, l_star = 0.f;
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
-            float4 o[kMergeBatch];
-            float2 ml[kMergeBatch];
-#pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j) {
-                const int c = min(c0 + j, nc - 1);   // past the end: re-read the last one, weight 0 below
-                const size_t pg = static_cast<size_t>(p0 + c) * G + g;
-                ml[j].x = fetch_f32(a.part_ml + pg * 2);
-                ml[j].y = fetch_f32(a.part_ml + pg * 2 + 1);
-                o[j].x = fetch_f32(a.part_o + pg * D + d);
-                o[j].y = fetch_f32(a.part_o + pg * D + d + 1);
-                o[j].z = fetch_f32(a.part_o + pg * D + d + 2);
-                o[j].w = fetch_f32(a.part_o + pg * D + d + 3);
-            }
-            float m_new = m_star;
-#pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j)
-                if (c0 + j < nc) m_new = fmaxf(m_new, ml[j].x);
-            const float keep = m_star == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_star - m_new);
-            l_star *= keep;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] *= keep;
-#pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j) {
-                const bool live = c0 + j < nc && ml[j].x != -INFINITY;
-                const float f = live ? __builtin_amdgcn_exp2f(ml[j].x - m_new) : 0.f;
-                l_star = fmaf(ml[j].y, f, l_star);
-                acc[0] = fmaf(o[j].x, f, acc[0]);
-                acc[1] = fmaf(o[j].y, f, acc[1]);
-                acc[2] = fmaf(o[j].z, f, acc[2]);
-                acc[3] = fmaf(o[j].w, f, acc[3]);
-            }
-            m_star = m_new;
-        }
-        const size_t oi = (static_cast<size_t>(b) * a.Hq + h * G + g) * D + d;
-        const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) store_out(a.out, a.out_dtype, oi + e, acc[e] * inv);
-        if (d == 0 && a.lse)
-            a.lse[b * a.Hq + h * G + g] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
-    }
+    const uint64_t w = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float(static_cast<uint32_t>(w)), __uint_as_float(static_cast<uint32_t>(w >> 32)));
 }
 
 // Partial results of cut pairs that a workgroup has finished but not yet handed over.  They
@@ -167,7 +121,7 @@ struct PendingParts {
 
 // Hand over the pending partials: publish them, wait until the stores are acknowledged,
 // count the workgroup in for each pair, and merge every pair for which it turned out to be
-// the last one (putting that pair's counter back to zero).  Called by all threads.
+// the last one (the log-sum-exp merge; that pair's counter goes back to zero).  Called by all threads.
 template <int D, int G>
 __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<D, G> &pend, int &n_pend)
 {
@@ -183,13 +137,76 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
         pend.last[threadIdx.x] = __hip_atomic_fetch_add(a.arrivals + pend.pair[threadIdx.x], 1, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT) == pend.n_chunks[threadIdx.x] - 1;
     __syncthreads();
-    for (int p = 0; p < n_pend; ++p) {
-        if (!pend.last[p]) continue;   // every partial of the pair was published before its workgroup counted in
-        const int pair = pend.pair[p], nc = pend.n_chunks[p], p0 = pend.first_part[p];
-        if (p0 >= 0 && p0 + nc <= a.n_parts) merge_pair<D, G>(a, pair / a.Hkv, pair % a.Hkv, p0, nc);
-        if (threadIdx.x == 0)   // ready for the next call on this workspace
-            __hip_atomic_store(a.arrivals + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Merge every pair for which this workgroup was the last to count in (all of that pair's
+    // partials were published before their workgroups counted in):
+    //   m* = max_c m_c,  l* = sum_c l_c 2^(m_c - m*),  out = sum_c o_c 2^(m_c - m*) / l*
+    // (exact in real arithmetic, so a cut pair gives what the whole pair would).  A thread owns
+    // four consecutive coordinates of one query head.  The loads of ALL pairs to merge are issued
+    // before any is used, so the hand-over costs one memory round trip, not one per pair.
+    constexpr int D4 = D / 4;
+    for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
+        const int g = idx / D4, d = (idx % D4) * 4;
+        float2 ml[kPend][kMergeBatch], o01[kPend][kMergeBatch], o23[kPend][kMergeBatch];
+#pragma unroll
+        for (int p = 0; p < kPend; ++p) {
+            if (p >= n_pend || !pend.last[p]) continue;
+            const int nc = pend.n_chunks[p], p0 = pend.first_part[p];
+            if (p0 < 0 || p0 + nc > a.n_parts) continue;
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                const size_t pg = static_cast<size_t>(p0 + min(j, nc - 1)) * G + g;   // past the end: weight 0 below
+                ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kPend; ++p) {
+            if (p >= n_pend || !pend.last[p]) continue;
+            const int nc = pend.n_chunks[p], p0 = pend.first_part[p], pair = pend.pair[p];
+            if (p0 < 0 || p0 + nc > a.n_parts) continue;
+            float m_star = -INFINITY, l_star = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
+                if (c0 > 0) {   // a pair in more than kMergeBatch pieces: fetch the next batch
+#pragma unroll
+                    for (int j = 0; j < kMergeBatch; ++j) {
+                        const size_t pg = static_cast<size_t>(p0 + min(c0 + j, nc - 1)) * G + g;
+                        ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                        o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                        o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                    }
+                }
+                float m_new = m_star;
+#pragma unroll
+                for (int j = 0; j < kMergeBatch; ++j)
+                    if (c0 + j < nc) m_new = fmaxf(m_new, ml[p][j].x);
+                const float keep = m_star == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_star - m_new);
+                l_star *= keep;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] *= keep;
+#pragma unroll
+                for (int j = 0; j < kMergeBatch; ++j) {
+                    const bool live = c0 + j < nc && ml[p][j].x != -INFINITY;
+                    const float f = live ? __builtin_amdgcn_exp2f(ml[p][j].x - m_new) : 0.f;
+                    l_star = fmaf(ml[p][j].y, f, l_star);
+                    acc[0] = fmaf(o01[p][j].x, f, acc[0]);
+                    acc[1] = fmaf(o01[p][j].y, f, acc[1]);
+                    acc[2] = fmaf(o23[p][j].x, f, acc[2]);
+                    acc[3] = fmaf(o23[p][j].y, f, acc[3]);
+                }
+                m_star = m_new;
+            }
+            const int b = pair / a.Hkv, h = pair % a.Hkv;
+            const size_t oi = (static_cast<size_t>(b) * a.Hq + h * G + g) * D + d;
+            const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) store_out(a.out, a.out_dtype, oi + e, acc[e] * inv);
+            if (d == 0 && a.lse)
+                a.lse[b * a.Hq + h * G + g] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
+        }
     }
+    if (threadIdx.x < n_pend && pend.last[threadIdx.x])   // ready for the next call on this workspace
+        __hip_atomic_store(a.arrivals + pend.pair[threadIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     n_pend = 0;
     __syncthreads();
 }

@@ -34,7 +34,7 @@ typedef __attribute__((ext_vector_type(4))) short i16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kTok = 16;      // tokens per tile (the M of the score MFMA, the K of the PV MFMA)
-constexpr int kStages = 4;    // tiles per wave resident in LDS
+constexpr int kStages = 2;    // tiles per wave resident in LDS: one being consumed, one in flight
 
 #define FAIRKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -137,21 +137,46 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
         }
     };
 
+    // Ring bookkeeping: the fetch cursor (f_*) runs ahead of the compute cursor, possibly into
+    // later items; `ahead` tiles are fetched and not yet consumed.
+    int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0, f_n = 0, f_tiles = 0;
+
+    // Early start: row and length of the slot's first item came with the kernel arguments, so
+    // its first tiles are requested before the item list has been read from memory.
+    const int n0 = static_cast<int>(a.first_n[blockIdx.x]);
+    const bool seeded = i_end > i_begin && n0 > 0;
+    if (seeded) {
+        const int64_t row_first = a.first_row[blockIdx.x];
+        f_n = n0;
+        f_tiles = tiles_of(n0);
+        while (ahead < kStages && f_t < f_tiles) {
+            fetch(row_first, f_n, f_t, f_stage);
+            f_stage = (f_stage + 1) % kStages;
+            ++f_t;
+            ++ahead;
+        }
+    }
+
     for (int batch = i_begin; batch < i_end; batch += kTable) {
         const int nb = min(kTable, i_end - batch);
+        const bool early = seeded && batch == i_begin;
         __syncthreads();                      // nobody still reads the previous table
         if (threadIdx.x < nb) {
             const fairkv_item it = a.items[batch + threadIdx.x];
             const bool ok = it.b >= 0 && it.b < a.B && it.h >= 0 && it.h < a.Hkv && it.row >= 0 && it.part >= 0 &&
                             it.part < a.n_parts && it.n_chunks >= 1;
-            table[threadIdx.x] = ItemRef{it.row, ok ? max(it.tok_count, 0) : 0, ok ? 1 : 0};   // a foreign item reads nothing
+            int n = ok ? max(it.tok_count, 0) : 0;      // a foreign item reads nothing
+            if (early && threadIdx.x == 0) n = n0;      // its tiles are already on their way
+            table[threadIdx.x] = ItemRef{it.row, n, ok ? 1 : 0};
         }
         __syncthreads();
 
-        // fetch cursor (runs ahead, possibly into later items) and the ring bookkeeping
-        int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0;
-        int f_n = __builtin_amdgcn_readfirstlane(table[0].n);
-        int f_tiles = tiles_of(f_n);
+        if (!early) {
+            f_item = 0;
+            f_t = 0;
+            f_n = __builtin_amdgcn_readfirstlane(table[0].n);
+            f_tiles = tiles_of(f_n);
+        }
         auto top_up = [&]() {
             while (ahead < kStages && f_item < nb) {
                 if (f_t < f_tiles) {
@@ -196,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 else if (later == 2) wait_vmcnt<2 * LOADS>();
                 else if (later == 1) wait_vmcnt<LOADS>();
                 else wait_vmcnt<0>();
-                static_assert(kStages == 4, "the wait ladder above is written for four stages");
+                static_assert(kStages <= 4, "the wait ladder above handles at most three later tiles");
 
                 const char *kst = ring + c_stage * STAGEB;
                 const char *vst = kst + TILEB;

@@ -81,13 +81,14 @@ extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32
 }
 
 extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, const fairkv_item *items,
-                                  int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                                  const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
+                                  int32_t n_slots,
                                   int32_t n_parts, void *workspace,
                                   size_t workspace_bytes, void *out, float *lse, int32_t B, int32_t Hq,
                                   int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
                                   void *hip_stream)
 {
-    if (!q || !k || !v || !items || !slot_ptr || !out) return FAIRKV_EINVAL;
+    if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
     if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0) return FAIRKV_EINVAL;
     if (Hq % Hkv != 0) return FAIRKV_EINVAL;
     if (n_parts < n_items) return FAIRKV_EINVAL;
@@ -95,6 +96,12 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     if (slot_ptr[0] != 0 || slot_ptr[n_slots] != n_items) return FAIRKV_EINVAL;
     for (int32_t j = 0; j < n_slots; ++j)
         if (slot_ptr[j] > slot_ptr[j + 1]) return FAIRKV_EINVAL;
+    for (int32_t i = 0; i < n_items; ++i) {
+        const fairkv_item &it = items_host[i];
+        if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
+        if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
+        if (it.part < it.chunk || it.part - it.chunk + it.n_chunks > n_parts) return FAIRKV_EINVAL;
+    }
     if (!(scale == scale) || std::isinf(scale)) return FAIRKV_EINVAL;
     if (in_dtype != FAIRKV_BF16 && in_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
     if (out_dtype != FAIRKV_BF16 && out_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
@@ -115,6 +122,15 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     a.v = v;
     a.items = items;
     for (int32_t j = 0; j <= n_slots; ++j) a.slot_ptr[j] = slot_ptr[j];
+    for (int32_t j = 0; j < n_slots; ++j) {
+        a.first_row[j] = 0;
+        a.first_n[j] = 0;
+        if (slot_ptr[j] == slot_ptr[j + 1]) continue;
+        const fairkv_item &it = items_host[slot_ptr[j]];
+        if (it.row + it.tok_count > static_cast<int64_t>(UINT32_MAX)) continue;   // does not fit: normal start
+        a.first_row[j] = static_cast<uint32_t>(it.row);
+        a.first_n[j] = static_cast<uint32_t>(it.tok_count);
+    }
     a.part_o = reinterpret_cast<float *>(ws);
     ws += align256(static_cast<size_t>(n_parts) * G * D * sizeof(float));
     a.part_ml = reinterpret_cast<float *>(ws);

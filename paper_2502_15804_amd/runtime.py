@@ -47,6 +47,6 @@ class DecodeLayer:
         self.lse = torch.empty((self.B, self.Hq), dtype=torch.float32, device=dev) if want_lse else None
 
     def run(self, stream=None):
-        fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.slot_ptr, self.plan.n_parts,
+        fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.items, self.plan.slot_ptr, self.plan.n_parts,
                            self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
         return self.out, self.lse

@@ -158,12 +158,26 @@ def test_decode_attn_validates_before_any_launch():
     fake = ctypes.c_void_p(0x1000)
 
     good_sp = np.array([0, 1], np.int32)
+    good_item = np.zeros(1, F.ITEM_DTYPE)
+    good_item["tok_count"], good_item["n_chunks"] = 5, 1
 
-    def call(q=fake, k=fake, v=fake, items=fake, n_items=1, sp=good_sp, n_slots=1, n_parts=1, ws=fake,
+    def item(**kw):
+        it = good_item.copy()
+        for k_, v_ in kw.items():
+            it[k_] = v_
+        return it
+
+    def call(q=fake, k=fake, v=fake, items=fake, ih=good_item, n_items=1, sp=good_sp, n_slots=1, n_parts=1, ws=fake,
              ws_bytes=1 << 30, out=fake, lse=None, B=1, Hq=8, Hkv=1, D=128, idt=0, odt=1, scale=0.1):
         spp = sp.ctypes.data if sp is not None else None
-        return L.fairkv_decode_attn(q, k, v, items, n_items, spp, n_slots, n_parts, ws, ws_bytes, out, lse,
+        ihp = ih.ctypes.data if ih is not None else None
+        return L.fairkv_decode_attn(q, k, v, items, ihp, n_items, spp, n_slots, n_parts, ws, ws_bytes, out, lse,
                                     B, Hq, Hkv, D, idt, odt, scale, None)
+
+    assert call(ih=None) == F.FAIRKV_EINVAL
+    for bad in (item(b=1), item(h=-1), item(row=-3), item(tok_count=-1), item(n_chunks=0), item(chunk=1),
+                item(part=1), item(n_chunks=2, chunk=1, part=0), item(n_chunks=2)):
+        assert call(ih=bad) == F.FAIRKV_EINVAL, bad
 
     assert call(q=None) == F.FAIRKV_EINVAL
     assert call(out=None) == F.FAIRKV_EINVAL
@@ -173,8 +187,8 @@ def test_decode_attn_validates_before_any_launch():
     assert call(n_slots=0) == F.FAIRKV_EINVAL
     assert call(sp=np.array([0, 2], np.int32)) == F.FAIRKV_EINVAL   # slot pointer does not end at n_items
     assert call(sp=np.array([1, 1], np.int32)) == F.FAIRKV_EINVAL
-    big = np.zeros(2000, np.int32); big[-1] = 1
-    assert call(sp=big, n_slots=1999) == F.FAIRKV_EUNSUPPORTED      # too many slots for the kernel arguments
+    big = np.zeros(322, np.int32); big[-1] = 1
+    assert call(sp=big, n_slots=321) == F.FAIRKV_EUNSUPPORTED      # too many slots for the kernel arguments
     assert call(n_items=0) == F.FAIRKV_EINVAL                      # every pair has at least one item
     assert call(Hq=7, Hkv=2) == F.FAIRKV_EINVAL
     assert call(n_parts=0) == F.FAIRKV_EINVAL                      # fewer parts than items
