@@ -139,6 +139,25 @@ def measured_traffic(workload):
     return None
 
 
+def spot_check(rot, n_layers=2, n_samples=48):
+    """After the timed region: sampled outputs of a few layers, as the timed launches left them,
+    against the oracle (the same launch configuration that was timed)."""
+    import numpy as np
+    import workloads as W
+    from oracle import attention as OA
+
+    worst = 0.0
+    rng = np.random.default_rng(0)
+    for li in sorted({0, len(rot.layers) - 1, len(rot.layers) // 2})[:max(1, n_layers + 1)]:
+        layer = rot.layers[li]
+        sel = rng.choice(rot.w.B * rot.w.Hq, size=min(n_samples, rot.w.B * rot.w.Hq), replace=False).astype(np.int32)
+        ro, _ = OA.attention(*(W.to_numpy_bits(t) for t in (layer.q, layer.k, layer.v)), rot.offs[li], rot.lens[li],
+                             rot.w.scale, sel=sel)
+        got = layer.out.float().cpu().numpy().astype(np.float64).reshape(-1, rot.w.D)
+        worst = max(worst, float(np.abs(got[sel] - ro.reshape(-1, rot.w.D)[sel]).max()))
+    return worst
+
+
 def cpu_baseline(rot, seconds):
     """The fp64 oracle, as it stands, on the host cores: whole layers of the same workload."""
     import workloads as W
@@ -219,6 +238,10 @@ def main():
         "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
                          "(Llama-3.3-70B, Section 5.2.2); other hardware, not this metric",
     }
+    rec["spot_check_max_abs_err"] = round(spot_check(rot), 6)
+    if not rec["spot_check_max_abs_err"] <= w.tol:
+        print(f"bench: outputs of the timed launches are off by {rec['spot_check_max_abs_err']}", file=sys.stderr)
+        sys.exit(1)
     if not a.no_extras:
         short = max(n_layers * 4, 64)
         for pol, key in ((0, "naive"), (1, "lpt_nosplit"), (2, "lpt_equal_split")):

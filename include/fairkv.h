@@ -100,7 +100,7 @@ typedef struct {
 } fairkv_plan_summary;
 
 /* Defaults: n_slots = n_compute_units, tile 16, min_chunk 32, max_split 256, oversub 2,
- * overhead_tokens 192 (measured on MI355X: an extra item in a slot costs about as much as
+ * overhead_tokens 256 (measured on MI355X: an extra item in a slot costs about as much as
  * streaming 200-300 tokens), policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
@@ -139,9 +139,11 @@ int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, int32_t Hkv, 
 
 /* Bytes of device workspace fairkv_decode_attn needs: fp32 partial outputs and softmax
  * statistics for n_parts items, plus one arrival counter per pair.  0 on bad arguments.
- * Layout: partial outputs, then statistics, then the counters, each region rounded up to
- * 256 bytes.  The workspace must be zero-filled once before its first use (the arrival
- * counters start at zero); every completed call leaves the counters at zero again. */
+ * Layout: the counters first (n_pairs int32, rounded up to 256 bytes), then statistics and
+ * partial outputs.  The first 256-byte-rounded 4 * n_pairs bytes must be zero before the
+ * first use (the arrival counters start at zero); every completed call leaves them zero
+ * again, whatever its plan, so calls with the same B * Hkv that are ordered on one stream
+ * may share one workspace. */
 size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D);
 
 /*
@@ -178,7 +180,7 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  *
  * Supported: D in {64, 128}; in_dtype BF16 or F32; G = Hq/Hkv in {1, 2, 4, 8};
  * n_slots <= FAIRKV_MAX_SLOTS (else FAIRKV_EUNSUPPORTED).
- * Calls that share a workspace must be ordered on one stream.
+ * Calls that share a workspace must have the same B * Hkv and be ordered on one stream.
  */
 int fairkv_decode_attn(const void *q, const void *k, const void *v,
                        const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,

@@ -70,8 +70,9 @@ size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
-// Workspace layout: part_o [n_parts][G][D] f32 | part_ml [n_parts][G][2] f32 | arrivals [n_pairs] i32,
-// each region starting on a 256-byte boundary.
+// Workspace layout: arrivals [n_pairs] i32 | part_ml [n_parts][G][2] f32 | part_o [n_parts][G][D] f32,
+// each region starting on a 256-byte boundary.  The counters come first so that their place does
+// not depend on n_parts: calls with different plans may then share one workspace.
 extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D)
 {
     if (n_parts < 0 || n_pairs < 1 || G < 1 || D < 1) return 0;
@@ -131,11 +132,11 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
         a.first_row[j] = static_cast<uint32_t>(it.row);
         a.first_n[j] = static_cast<uint32_t>(it.tok_count);
     }
-    a.part_o = reinterpret_cast<float *>(ws);
-    ws += align256(static_cast<size_t>(n_parts) * G * D * sizeof(float));
+    a.arrivals = reinterpret_cast<int32_t *>(ws);
+    ws += align256(static_cast<size_t>(B) * Hkv * sizeof(int32_t));
     a.part_ml = reinterpret_cast<float *>(ws);
     ws += align256(static_cast<size_t>(n_parts) * G * 2 * sizeof(float));
-    a.arrivals = reinterpret_cast<int32_t *>(ws);
+    a.part_o = reinterpret_cast<float *>(ws);
     a.out = out;
     a.lse = lse;
     a.B = B;

@@ -33,8 +33,8 @@ def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison
         if poison:
             layer.out.fill_(float("nan"))
             layer.lse.fill_(float("nan"))
-            counters = -(-lens.size * 4 // 256) * 256          # the last region of the workspace
-            layer.workspace[: layer.workspace.numel() - counters].fill_(0xFF)
+            counters = -(-lens.size * 4 // 256) * 256          # the first region of the workspace
+            layer.workspace[counters:].fill_(0xFF)
         layer.run()
         torch.cuda.synchronize()
     return layer.out.float().cpu().numpy().astype(np.float64), layer.lse.cpu().numpy().astype(np.float64), layer
@@ -185,3 +185,93 @@ def test_full_size_workloads_every_output(name):
             naive.run()
             torch.cuda.synchronize()
             assert np.abs(naive.out.cpu().numpy().astype(np.float64) - ro).max() <= w.tol
+
+
+def test_slot_lists_longer_than_the_item_table():
+    # 200 pairs on 2 slots: 100 items per slot, so the kernel walks its list in more than one table fill
+    rng = np.random.default_rng(21)
+    B, Hkv, G = 25, 8, 4
+    lens = rng.integers(0, 90, size=(B, Hkv)).astype(np.int32)
+    w, off, q, k, v = make_case(B, Hkv * G, Hkv, 128, "bf16", lens, seed=9, gap_rows=1)
+    for policy in (0, 3):
+        err, layer = check(w, q, k, v, off, lens, policy=policy, n_slots=2, calls=2)
+        assert np.diff(layer.plan.slot_ptr).max() > 64
+
+
+def test_many_cut_pieces_per_slot_and_per_pair():
+    # equal split over few slots: every slot holds many pieces of cut pairs (more than the pending
+    # buffer), and the long pair is in more pieces than one merge batch
+    lens = np.array([[9000, 700, 40], [33, 2500, 1]], np.int32)
+    w, off, q, k, v = make_case(2, 24, 3, 128, "bf16", lens, seed=10)
+    err, layer = check(w, q, k, v, off, lens, policy=2, n_slots=3, oversub=6, min_chunk=64, calls=2)
+    assert int(layer.plan.items["n_chunks"].max()) > 8 and layer.plan.n_items > 20
+    err, layer = check(w, q, k, v, off, lens, policy=3, n_slots=40, min_chunk=32, overhead_tokens=0, calls=2)
+    assert int(layer.plan.items["n_chunks"].max()) > 8
+    # the cap on pieces per pair (eq. 3) leaves one very long last piece
+    err, layer = check(w, q, k, v, off, lens, policy=3, n_slots=40, min_chunk=32, overhead_tokens=0, max_split=3)
+    assert int(layer.plan.items["n_chunks"].max()) == 3
+
+
+def test_longest_supported_head_and_most_slots():
+    rng = np.random.default_rng(22)
+    lens = rng.integers(1, 400, size=(4, 8)).astype(np.int32)
+    lens[1, 3] = 32768
+    w, off, q, k, v = make_case(4, 64, 8, 128, "bf16", lens, seed=11)
+    for n_slots in (256, 320):
+        err, layer = check(w, q, k, v, off, lens, policy=3, n_slots=n_slots)
+    assert err < 5e-3
+
+
+def test_hip_graph_replays_match_eager():
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    w = W.WORKLOADS["llama70b"]
+    lens = W.lens("llama70b", layer=2)[:4]
+    small = W.Workload("g", 4, w.Hq, w.Hkv, w.D, w.dtype, 1, w.tol, "")
+    off, total = W.packed_offsets(lens)
+    q, k, v = W.make_qkv(small, total, seed=3)
+    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, small.scale)
+    layer.run()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        layer.run()
+    kn, vn = W.to_numpy_bits(k), W.to_numpy_bits(v)
+    for rep in range(3):
+        # eager work and a new query between the replays
+        qr = (torch.randn(q.shape, generator=torch.Generator().manual_seed(100 + rep)) * (1 + rep)).to(torch.bfloat16)
+        layer.q.copy_(qr.cuda())
+        layer.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = layer.out.cpu().numpy().astype(np.float64)
+        ro, _ = OA.attention(W.to_numpy_bits(qr), kn, vn, off, lens, small.scale)
+        assert np.abs(got - ro).max() <= small.tol, rep
+        layer.run()                      # the same step eagerly: bit-identical to the replay
+        torch.cuda.synchronize()
+        assert np.array_equal(layer.out.cpu().numpy().astype(np.float64), got)
+
+
+def test_layers_sharing_one_workspace_on_one_stream():
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    F = _F()
+    w = W.WORKLOADS["mistral24b"]
+    small = W.Workload("s", 6, w.Hq, w.Hkv, w.D, w.dtype, 1, w.tol, "")
+    cases, need = [], 0
+    for li in range(3):
+        lens = W.lens("mistral24b", layer=li)[:6]
+        off, total = W.packed_offsets(lens)
+        q, k, v = W.make_qkv(small, total, seed=li)
+        plan = F.fairkv_plan(lens, off, 6, small.Hkv, F.fairkv_default_params(256))
+        need = max(need, F.fairkv_workspace_bytes(plan.n_parts, 6 * small.Hkv, small.G, small.D))
+        cases.append((lens, off, q, k, v))
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    layers = [DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, small.scale, workspace=ws, want_lse=False)
+              for lens, off, q, k, v in cases]
+    for _ in range(2):
+        for l in layers:
+            l.run()                        # back to back, no synchronisation in between
+    torch.cuda.synchronize()
+    for l, (lens, off, q, k, v) in zip(layers, cases):
+        ro, _ = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, small.scale)
+        assert np.abs(l.out.cpu().numpy().astype(np.float64) - ro).max() <= small.tol
