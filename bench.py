@@ -38,6 +38,10 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the policy comparison and the CPU baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--latency-model", action="store_true",
+                    help="instead of the benchmark: decode latency of one Llama-70B-shaped layer against batch size "
+                         "and against a uniform per-head budget (the paper's Section 3.2 / Figure 2 experiment), "
+                         "with least-squares lines L = alpha*B + beta and L = gamma*C + delta")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -158,6 +162,69 @@ def spot_check(rot, n_layers=2, n_samples=48):
     return worst
 
 
+def latency_model(seed=0):
+    """Section 3.2 of the paper on this GPU: one layer (64 query / 8 KV heads, D=128, bf16), every head with the
+    same budget C, batch B; time per decode step through the whole path (plan resident, one launch)."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_15804_amd.runtime import DecodeLayer
+
+    budgets, batches = (128, 256, 512, 1024), (32, 64, 128, 256, 512)
+    table = {}
+    for B in batches:
+        for C in budgets:
+            w = W.Workload("uniform", B, 64, 8, 128, "bf16", 1, 1e-2, "")
+            lens = np.full((B, 8), C, np.int32)
+            off, total = W.packed_offsets(lens)
+            bytes_layer = W.algorithmic_bytes(w, lens)
+            n_buf = max(2, min(16, int(1.5e9 // bytes_layer) + 1))      # rotate past the memory-side cache
+            layers = []
+            for i in range(n_buf):
+                q, k, v = W.make_qkv(w, total, seed=seed, layer=i, device="cuda")
+                layers.append(DecodeLayer(q, k, v, off, lens, w.scale, want_lse=False))
+            g = torch.cuda.CUDAGraph()
+            for l in layers:
+                l.run()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g):
+                for l in layers:
+                    l.run()
+            reps = max(3, int(2e-3 / (n_buf * bytes_layer / 4e12)))
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / (reps * n_buf)
+            table[(B, C)] = (us, bytes_layer / us / 1e3)
+            del layers, g
+            torch.cuda.empty_cache()
+
+    def fit(xs, ys):
+        A = np.vstack([xs, np.ones(len(xs))]).T
+        (a, b), res, *_ = np.linalg.lstsq(A, ys, rcond=None)
+        ss = float(((ys - ys.mean()) ** 2).sum())
+        r2 = 1.0 - float(((A @ [a, b] - ys) ** 2).sum()) / ss if ss > 0 else 1.0
+        return float(a), float(b), r2
+
+    rec = {"experiment": "decode latency of one layer vs batch size and vs per-head budget (paper Section 3.2)",
+           "shape": "64 query / 8 KV heads, D=128, bf16, uniform budget per head", "unit": "us per layer",
+           "latency_us": {f"B={B}": {f"C={C}": round(table[(B, C)][0], 2) for C in budgets} for B in batches},
+           "GBs": {f"B={B}": {f"C={C}": round(table[(B, C)][1]) for C in budgets} for B in batches},
+           "vs_batch": {}, "vs_budget": {}}
+    for C in budgets:
+        a_, b_, r2 = fit(np.array(batches, float), np.array([table[(B, C)][0] for B in batches]))
+        rec["vs_batch"][f"C={C}"] = {"alpha_us_per_seq": round(a_, 4), "beta_us": round(b_, 2), "r2": round(r2, 5)}
+    for B in batches:
+        a_, b_, r2 = fit(np.array(budgets, float), np.array([table[(B, C)][0] for C in budgets]))
+        rec["vs_budget"][f"B={B}"] = {"gamma_us_per_token": round(a_, 5), "delta_us": round(b_, 2), "r2": round(r2, 5)}
+    return rec
+
+
 def cpu_baseline(rot, seconds):
     """The fp64 oracle, as it stands, on the host cores: whole layers of the same workload."""
     import workloads as W
@@ -204,6 +271,9 @@ def main():
     if os.environ.get("FAIRKV_LIB"):        # A/B runs against another build of the library
         F.LIB_PATH = os.environ["FAIRKV_LIB"]
     F.lib()
+    if a.latency_model:
+        print(json.dumps(latency_model(a.seed)))
+        return
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers
     overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens")
