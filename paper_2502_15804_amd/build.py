@@ -25,6 +25,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA accumulators in ordinary vector registers: the softmax rescales them with vector
+           # instructions, and the accumulation-register form costs a copy in and out per tile
+           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
            "-Wall", "-Wextra", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
            "-I", os.path.join(ROOT, "include"), "-x", "hip", *SOURCES, "-o", LIB]
     if verbose:

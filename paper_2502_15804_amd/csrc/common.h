@@ -78,8 +78,10 @@ struct DecodeArgs {
     // What a workgroup needs before it has read anything from memory, riding in the kernel arguments:
     int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1])
     uint32_t first_row[FAIRKV_MAX_SLOTS];     // first K/V row of slot j's first item ...
-    uint32_t first_n[FAIRKV_MAX_SLOTS];       // ... and its token count; 0 = no early start for this slot
+    uint32_t first_np[FAIRKV_MAX_SLOTS];      // ... its pair b*Hkv+h in bits 8..31 and min(tok_count, kEarlyTok) in
+                                              // bits 0..7; 0 = no early start for this slot
 };
+constexpr int kEarlyTok = 192;            // tokens of a slot's first item that the early start may request
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
 // Layout facts shared by the stages.  A row of K or V is LPR 16-byte pieces; one wave-wide
@@ -119,6 +121,14 @@ struct PendingParts {
     int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend], last[kPend];
 };
 
+// s_waitcnt vmcnt(0), once as an instruction the compiler accounts for (simm16 of gfx9: vmcnt 0,
+// expcnt 7 and lgkmcnt 15 = no wait) and once as a fence for its own reordering of memory operations.
+__device__ __forceinline__ void drain_vmem()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // Hand over the pending partials: publish them, wait until the stores are acknowledged,
 // count the workgroup in for each pair, and merge every pair for which it turned out to be
 // the last one (the log-sum-exp merge; that pair's counter goes back to zero).  Called by all threads.
@@ -131,7 +141,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
         for (int idx = threadIdx.x; idx < G * D; idx += kThreads) publish_f32(a.part_o + base * D + idx, pend.o[p][idx]);
         if (threadIdx.x < G * 2) publish_f32(a.part_ml + base * 2 + threadIdx.x, pend.ml[p][threadIdx.x]);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have reached the shared level ...
+    drain_vmem();                                      // this thread's stores have reached the shared level ...
     __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
     if (threadIdx.x < n_pend)
         pend.last[threadIdx.x] = __hip_atomic_fetch_add(a.arrivals + pend.pair[threadIdx.x], 1, __ATOMIC_RELAXED,
@@ -208,6 +218,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
     if (threadIdx.x < n_pend && pend.last[threadIdx.x])   // ready for the next call on this workspace
         __hip_atomic_store(a.arrivals + pend.pair[threadIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     n_pend = 0;
+    drain_vmem();     // the compiler stops tracking the loads above: no guard waits on their registers later on
     __syncthreads();
 }
 

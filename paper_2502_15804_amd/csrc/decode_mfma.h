@@ -9,20 +9,29 @@
 // softmax of 4 scores per lane per tile.
 //
 // Shapes.  A wave works on tiles of 16 tokens.  The G query heads sit in the N dimension,
-// padded with zero queries to 16:
+// padded to 16 with copies of the last head (their columns are computed and never stored):
 //     S^T[token][head] = K[token][:] . q[head][:]       4 x mfma_16x16x32 (contract over d)
 //     O^T[d][head]    += V^T[d][token] P[token][head]   8 x mfma_16x16x16 (contract over tokens)
-// A lane owns head (lane % 16) in the scores, in P and in O^T alike, so the running
+// A lane owns head (lane % 16) in the scores, in P and in O^T alike, so the reference
 // maximum, the rescaling and the bf16 weights never leave the lane.
 //
-// Data path.  K and V rows go from HBM straight into LDS (global_load_lds_dwordx4, no
-// registers), each wave filling its own ring of kStages tiles, so up to kStages-1 tiles
-// per wave are in flight while one is being consumed.  The workgroup is persistent: it
-// walks the items the planner gave its slot, and a wave's ring runs on into the next item
-// while the current one is being finished, so only the first tile of a slot waits for HBM.  16-byte pieces are stored
-// XOR-swizzled (the swizzle is applied to the global address a lane fetches, since the
-// LDS slot of a lane is fixed) so that the row-per-lane reads of K and the transposing
-// reads of V (ds_read_b64_tr_b16) spread over all banks.
+// One wave per SIMD means nothing hides a wave's own latencies, so the work on a tile is
+// laid out as one LDS round trip (all K and V reads issued together), the score MFMAs, a
+// handful of vector instructions and the PV MFMAs.  To that end the softmax keeps a stale
+// reference maximum m per head: weights are 2^(s - m) with m raised (and O, l rescaled,
+// which needs the only cross-lane exchange) only when some score exceeds m by more than
+// kBump, so the weights stay below 2^kBump and the result is the same softmax.
+//
+// Data path.  K and V rows, the query rows of each item and the slot's item list go from
+// HBM straight into LDS (global_load_lds_dwordx4, no registers), each wave filling its own
+// ring of kStages tiles.  Inside the item loop there is no load the compiler knows about: it
+// would answer each with an s_waitcnt vmcnt(0) that also waits for every tile in flight,
+// i.e. one exposed memory latency per item.  The workgroup is persistent: it walks the
+// items the planner gave its slot, and a wave's ring runs on into the next item while the
+// current one is being finished, so only the first tile of a slot waits for HBM.  16-byte
+// pieces are stored XOR-swizzled (the swizzle is applied to the global address a lane
+// fetches, since the LDS slot of a lane is fixed) so that the row-per-lane reads of K and
+// the transposing reads of V (ds_read_b64_tr_b16) spread over all banks.
 #pragma once
 #include "common.h"
 
@@ -34,18 +43,19 @@ typedef __attribute__((ext_vector_type(4))) short i16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kTok = 16;      // tokens per tile (the M of the score MFMA, the K of the PV MFMA)
-constexpr int kStages = 2;    // tiles per wave resident in LDS: one being consumed, one in flight
+constexpr int kStages = 3;    // tiles per wave resident in LDS: one being consumed, the others in flight
+constexpr float kBump = 8.f;  // log2 units a score may exceed the reference maximum before it is raised
 
 #define FAIRKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-// One wave-wide direct load HBM -> LDS: lane j's 16 bytes at `src` land at LDS byte address
-// lds_base + 16 j (lds_base is wave-uniform and travels in M0).  Written as inline assembly
-// so that the compiler does not track it: it would otherwise drain ALL outstanding loads
-// (s_waitcnt vmcnt(0)) before any LDS read, which defeats the multi-stage ring.  The waits
-// are placed by hand with wait_vmcnt below.
-__device__ __forceinline__ void load16_to_lds(const void *src, uint32_t lds_base)
+// One wave-wide direct load HBM -> LDS: lane j's 16 bytes at base + off land at LDS byte
+// address lds_base + 16 j (base and lds_base are wave-uniform; lds_base travels in M0).
+// Written as inline assembly so that the compiler does not track it: it would otherwise
+// drain ALL outstanding loads (s_waitcnt vmcnt(0)) before any LDS read, which defeats the
+// multi-stage ring.  The waits are placed by hand with wait_vmcnt below.
+__device__ __forceinline__ void load16_to_lds(const void *base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
 // s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt is split
@@ -57,20 +67,53 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// LDS table of the slot's items: what the waves need of a fairkv_item, 16 bytes each.
-struct ItemRef {
+// Wait until at most `tiles` tile fetches (LOADS loads each) and `qs` query-block fetches
+// (QL loads each) are outstanding, i.e. everything requested before them has landed.
+template <int LOADS, int QL>
+__device__ __forceinline__ void wait_all_but(int tiles, int qs)
+{
+    static_assert(3 * (LOADS + QL) < 64, "vmcnt is a 6-bit counter");
+    switch (tiles * 4 + qs) {
+    case 4: wait_vmcnt<LOADS>(); break;
+    case 5: wait_vmcnt<LOADS + QL>(); break;
+    case 8: wait_vmcnt<2 * LOADS>(); break;
+    case 9: wait_vmcnt<2 * LOADS + QL>(); break;
+    case 10: wait_vmcnt<2 * LOADS + 2 * QL>(); break;
+    case 12: wait_vmcnt<3 * LOADS>(); break;
+    case 13: wait_vmcnt<3 * LOADS + QL>(); break;
+    case 14: wait_vmcnt<3 * LOADS + 2 * QL>(); break;
+    case 15: wait_vmcnt<3 * LOADS + 3 * QL>(); break;
+    default: wait_vmcnt<0>(); break;
+    }
+}
+
+__device__ __forceinline__ int64_t uniform64(int64_t x)   // a wave-uniform value, moved to scalar registers
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(x));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(x >> 32));
+    return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// LDS copy of the slot's items: what the waves need of a fairkv_item, plus the checked length.
+struct ItemSlot {
     int64_t row;
-    int32_t n;
-    int32_t valid;   // 0: the item does not belong to this problem and is skipped
+    int32_t n;        // tokens to read; 0 for an item that does not belong to this problem
+    int32_t valid;    // 0: such an item; it is skipped
+    int32_t b, h, chunk, n_chunks, part;
+    int32_t pad[3];
 };
-constexpr int kTable = 64;   // items per table fill; longer slot lists are walked in batches
+static_assert(sizeof(ItemSlot) == 48, "item table entry");
+constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches 32); longer slot lists go in batches
 
 template <int D, int G>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
     static_assert(G >= 1 && G <= 16, "query heads of a group fit the N dimension");
-    constexpr int ROWB = D * 2;              // bytes per K or V row
+    constexpr int kEarly = kStages < 3 ? kStages : 3;   // tiles per wave the early start may request
+    static_assert(kStages >= 2 && kStages <= 4 && kEarlyTok >= kEarly * kWaves * kTok && kEarlyTok < 256, "ring, early start");
+    static_assert(sizeof(fairkv_item) == 32, "two 16-byte pieces per item");
+    constexpr int ROWB = D * 2;              // bytes per K, V or q row
     constexpr int PPR = ROWB / 16;           // 16-byte pieces per row: 16 or 8
     constexpr int RPI = 64 / PPR;            // rows one wave-wide 16-byte load covers
     constexpr int LPT = kTok / RPI;          // wave-wide loads per K (or V) tile
@@ -79,11 +122,17 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     constexpr int LOADS = 2 * LPT;           // vector-memory instructions per stage
     constexpr int NSL = D / 32;              // d slices of the score contraction
     constexpr int NDB = D / 16;              // 16-wide d blocks of the output
+    constexpr int QBYTES = G * ROWB;         // the G query rows of a group are contiguous in q
+    constexpr int QL = (QBYTES + 1023) / 1024;   // wave-wide loads per query block
+    constexpr int QBUF = QL * 1024;
 
     __shared__ __attribute__((aligned(1024))) char lds[kWaves * kStages * STAGEB];
+    __shared__ __attribute__((aligned(1024))) char qlds[kWaves * kStages * QBUF];   // a query block per ring stage: the tiles in
+                                                                                    // the ring may belong to kStages different items
+    __shared__ __attribute__((aligned(1024))) fairkv_item raw[kTable];        // items as fetched
+    __shared__ __attribute__((aligned(16))) ItemSlot table[kTable];           // items as checked
     __shared__ __attribute__((aligned(16))) float st_o[kWaves * G * D];
     __shared__ float st_ml[kWaves * G * 2];
-    __shared__ __attribute__((aligned(16))) ItemRef table[kTable];
     __shared__ PendingParts<D, G> pend;
     int n_pend = 0;
 
@@ -93,10 +142,36 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     const int lq = lane >> 4;       // which quarter of the contraction index this lane feeds
 
     const int i_begin = a.slot_ptr[blockIdx.x], i_end = a.slot_ptr[blockIdx.x + 1];
+    if (i_end <= i_begin) return;   // an idle slot
     const uint32_t ring_lds =
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(lds))) + wave * (kStages * STAGEB);
     const char *ring = lds + wave * (kStages * STAGEB);
+    const uint32_t q_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(qlds))) + wave * (kStages * QBUF);
+    const char *q_ring = qlds + wave * (kStages * QBUF);
+    const uint32_t raw_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(raw))) + wave * 1024;
+
+    // Lane j of load i of a tile fills LDS slot (row i*RPI + j/PPR, column j%PPR); the piece it
+    // fetches is column ^ swizzle(row).  Byte offsets of that piece inside a full K and V tile:
     const int ld_row = lane / PPR, ld_col = lane % PPR;
+    uint32_t k_off[LPT], v_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int r = i * RPI + ld_row;
+        k_off[i] = r * ROWB + (ld_col ^ (r % PPR)) * 16;
+        v_off[i] = r * ROWB + (ld_col ^ ((2 * r) % PPR)) * 16;
+    }
+    // ... and where a lane reads its operands: the K row l16 (pieces 4 s + lq) and, through the
+    // transposing read, 4 d's of V row 4 lq + l16/4 (lane j of a 16-lane group receives element
+    // j%4 of the rows its lanes 4i + j/4 address).
+    uint32_t k_rd[NSL], v_rd[NDB];
+#pragma unroll
+    for (int s = 0; s < NSL; ++s) k_rd[s] = l16 * ROWB + ((4 * s + lq) ^ (l16 % PPR)) * 16;
+    {
+        const int vrow = 4 * lq + (l16 >> 2), vsub = l16 & 3;
+#pragma unroll
+        for (int nb_ = 0; nb_ < NDB; ++nb_)
+            v_rd[nb_] = TILEB + vrow * ROWB + (((2 * nb_ + (vsub >> 1)) ^ ((2 * vrow) % PPR)) * 16) + (vsub & 1) * 8;
+    }
 
     // tiles of an n-token item that fall to this wave: tiles wave, wave + kWaves, ...
     auto tiles_of = [&](int n) {
@@ -104,9 +179,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
         return n_tiles > wave ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     };
 
-    // Fetch of this wave's t-th tile of an item into one stage.  Lane j of load i fills LDS slot
-    // (row i*RPI + j/PPR, column j%PPR); the piece it fetches is column ^ swizzle(row).  Rows past
-    // the end of the item re-read its last row, so that every stage costs exactly LOADS loads.
+    // Fetch of this wave's t-th tile of an item into one stage: always exactly LOADS loads.
+    // Rows past the end of the item re-read its last row (finite data with weight 0).
     auto fetch = [&](int64_t row, int n, int t, int stage) {
         const int tok0 = (wave + t * kWaves) * kTok;
         const int last = n - 1 - tok0;
@@ -114,175 +188,213 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
         const char *vbase = static_cast<const char *>(a.v) + (row + tok0) * ROWB;
         const uint32_t kst = ring_lds + stage * STAGEB;
         const uint32_t vst = kst + TILEB;
+        if (last >= kTok - 1) {
 #pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            const int r = i * RPI + ld_row;
-            const int rc = min(r, last);
-            const int kcol = ld_col ^ (r % PPR);
-            const int vcol = ld_col ^ ((2 * r) % PPR);
-            load16_to_lds(kbase + rc * ROWB + kcol * 16, kst + i * 1024);
-            load16_to_lds(vbase + rc * ROWB + vcol * 16, vst + i * 1024);
+            for (int i = 0; i < LPT; ++i) {
+                load16_to_lds(kbase, k_off[i], kst + i * 1024);
+                load16_to_lds(vbase, v_off[i], vst + i * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int r = i * RPI + ld_row;
+                const int rc = min(r, last);
+                load16_to_lds(kbase, rc * ROWB + (ld_col ^ (r % PPR)) * 16, kst + i * 1024);
+                load16_to_lds(vbase, rc * ROWB + (ld_col ^ ((2 * r) % PPR)) * 16, vst + i * 1024);
+            }
         }
     };
 
-    // q of an item as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8]; heads >= G are zero.
-    auto load_q = [&](const fairkv_item &it, bf16x8_t (&qb)[NSL]) {
-        const uint4 *qrow = reinterpret_cast<const uint4 *>(
-            static_cast<const char *>(a.q) + (static_cast<size_t>(it.b) * a.Hq + it.h * G + min(l16, G - 1)) * ROWB);
+    // Fetch of the G query rows of pair (b, h) into one of the wave's q buffers: exactly QL loads.
+    auto fetch_q = [&](int b, int h, int buf) {
+        const char *src = static_cast<const char *>(a.q) + (static_cast<size_t>(b) * a.Hq + h * G) * ROWB;
 #pragma unroll
-        for (int s = 0; s < NSL; ++s) {
-            uint4 w = qrow[4 * s + lq];
-            if (l16 >= G) w = make_uint4(0u, 0u, 0u, 0u);
-            qb[s] = __builtin_bit_cast(bf16x8_t, w);
-        }
+        for (int i = 0; i < QL; ++i) load16_to_lds(src, min(i * 1024 + lane * 16, QBYTES - 16), q_lds + buf * QBUF + i * 1024);
+    };
+
+    // Fetch of this wave's 32 of the kTable items that start at `first`: one load.  Past the end of
+    // the slot's list the last item is read again.
+    auto fetch_items = [&](int first) {
+        const int rel = min(32 * wave + (lane >> 1), i_end - 1 - first);
+        load16_to_lds(a.items + first, rel * 32 + (lane & 1) * 16, raw_lds);
     };
 
     // Ring bookkeeping: the fetch cursor (f_*) runs ahead of the compute cursor, possibly into
-    // later items; `ahead` tiles are fetched and not yet consumed.
-    int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0, f_n = 0, f_tiles = 0;
+    // later items; `ahead` tiles are fetched and not yet consumed.  The query block of an item is
+    // requested right before the item's first tile, into the q buffer of that tile's stage, so it
+    // has landed when the tile has; bit s of q_mask says that the tile now in stage s came with one.
+    int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0, f_n = 0, f_tiles = 0, f_b = 0, f_h = 0;
+    int64_t f_row = 0;
+    uint32_t q_mask = 0;
+    auto fetch_next = [&]() {      // the cursor's tile, f_t < f_tiles
+        if (f_t == 0) {
+            fetch_q(f_b, f_h, f_stage);
+            q_mask |= 1u << f_stage;
+        }
+        fetch(f_row, f_n, f_t, f_stage);
+        f_stage = f_stage + 1 == kStages ? 0 : f_stage + 1;
+        ++f_t;
+        ++ahead;
+    };
 
-    // Early start: row and length of the slot's first item came with the kernel arguments, so
-    // its first tiles are requested before the item list has been read from memory.
-    const int n0 = static_cast<int>(a.first_n[blockIdx.x]);
-    const bool seeded = i_end > i_begin && n0 > 0;
+    // Early start: the kernel arguments carry pair, first row and the first kEarlyTok tokens' worth
+    // of the length of the slot's first item, so the item list, the first query block and the first
+    // tiles are all requested at once, before anything has come back from memory.
+    fetch_items(i_begin);
+    const uint32_t np0 = a.first_np[blockIdx.x];
+    const int n0 = static_cast<int>(np0 & 0xffu);
+    const bool seeded = n0 > 0;
     if (seeded) {
-        const int64_t row_first = a.first_row[blockIdx.x];
+        const int pair0 = static_cast<int>(np0 >> 8);
+        f_b = pair0 / a.Hkv;
+        f_h = pair0 - f_b * a.Hkv;
+        f_row = a.first_row[blockIdx.x];
         f_n = n0;
         f_tiles = tiles_of(n0);
-        while (ahead < kStages && f_t < f_tiles) {
-            fetch(row_first, f_n, f_t, f_stage);
-            f_stage = (f_stage + 1) % kStages;
-            ++f_t;
-            ++ahead;
-        }
+        while (ahead < kEarly && f_t < f_tiles) fetch_next();
     }
 
     for (int batch = i_begin; batch < i_end; batch += kTable) {
         const int nb = min(kTable, i_end - batch);
         const bool early = seeded && batch == i_begin;
-        __syncthreads();                      // nobody still reads the previous table
+        if (batch != i_begin) {
+            __syncthreads();                  // nobody still reads the previous table
+            fetch_items(batch);
+        }
+        // the items have landed once only what was requested after them is outstanding
+        wait_all_but<LOADS, QL>(ahead, __builtin_popcount(q_mask));
+        __syncthreads();
         if (threadIdx.x < nb) {
-            const fairkv_item it = a.items[batch + threadIdx.x];
+            const fairkv_item it = raw[threadIdx.x];
             const bool ok = it.b >= 0 && it.b < a.B && it.h >= 0 && it.h < a.Hkv && it.row >= 0 && it.part >= 0 &&
-                            it.part < a.n_parts && it.n_chunks >= 1;
+                            it.part < a.n_parts && it.n_chunks >= 1 && it.chunk >= 0 && it.chunk <= it.part;
             int n = ok ? max(it.tok_count, 0) : 0;      // a foreign item reads nothing
-            if (early && threadIdx.x == 0) n = n0;      // its tiles are already on their way
-            table[threadIdx.x] = ItemRef{it.row, n, ok ? 1 : 0};
+            if (early && threadIdx.x == 0)              // its first tiles are on their way, as many as n0 said
+                n = n0 < kEarlyTok ? n0 : max(n, kEarlyTok);
+            table[threadIdx.x] = ItemSlot{it.row, n, ok ? 1 : 0, ok ? it.b : 0, ok ? it.h : 0,
+                                          it.chunk, it.n_chunks, it.part, {0, 0, 0}};
         }
         __syncthreads();
 
-        if (!early) {
-            f_item = 0;
+        auto seek = [&](int item) {           // point the fetch cursor at an item of the table
+            f_item = item;
             f_t = 0;
+            if (item < nb) {
+                f_row = uniform64(table[item].row);
+                f_n = __builtin_amdgcn_readfirstlane(table[item].n);
+                f_b = __builtin_amdgcn_readfirstlane(table[item].b);
+                f_h = __builtin_amdgcn_readfirstlane(table[item].h);
+            } else {
+                f_n = 0;
+            }
+            f_tiles = tiles_of(f_n);
+        };
+        if (early) {                          // the cursor is already inside item 0: learn its full length
             f_n = __builtin_amdgcn_readfirstlane(table[0].n);
             f_tiles = tiles_of(f_n);
+        } else {
+            seek(0);
         }
         auto top_up = [&]() {
             while (ahead < kStages && f_item < nb) {
-                if (f_t < f_tiles) {
-                    const int64_t row = table[f_item].row;
-                    fetch(row, f_n, f_t, f_stage);
-                    f_stage = (f_stage + 1) % kStages;
-                    ++f_t;
-                    ++ahead;
-                } else {
-                    ++f_item;
-                    f_t = 0;
-                    f_n = f_item < nb ? __builtin_amdgcn_readfirstlane(table[f_item].n) : 0;
-                    f_tiles = tiles_of(f_n);
-                }
+                if (f_t < f_tiles)
+                    fetch_next();
+                else
+                    seek(f_item + 1);
             }
         };
         top_up();
 
-        bf16x8_t q_next[NSL];
-        if (__builtin_amdgcn_readfirstlane(table[0].valid)) load_q(a.items[batch], q_next);
-
         for (int ci = 0; ci < nb; ++ci) {
-            const fairkv_item it = a.items[batch + ci];
+            fairkv_item it;
+            it.row = 0;
+            it.tok_count = 0;
+            it.b = __builtin_amdgcn_readfirstlane(table[ci].b);
+            it.h = __builtin_amdgcn_readfirstlane(table[ci].h);
+            it.chunk = __builtin_amdgcn_readfirstlane(table[ci].chunk);
+            it.n_chunks = __builtin_amdgcn_readfirstlane(table[ci].n_chunks);
+            it.part = __builtin_amdgcn_readfirstlane(table[ci].part);
             const int n = __builtin_amdgcn_readfirstlane(table[ci].n);
             const int my_tiles = tiles_of(n);
             bf16x8_t qb[NSL];
 #pragma unroll
-            for (int s = 0; s < NSL; ++s) qb[s] = q_next[s];
-            if (ci + 1 < nb && __builtin_amdgcn_readfirstlane(table[ci + 1].valid))
-                load_q(a.items[batch + ci + 1], q_next);   // lands while this item streams
+            for (int s = 0; s < NSL; ++s) qb[s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
 
             f32x4_t o[NDB];
 #pragma unroll
             for (int nb_ = 0; nb_ < NDB; ++nb_) o[nb_] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            float m_run = -INFINITY, l_run = 0.f;
+            float m_run = -INFINITY, l_run = 0.f;   // reference maximum of the lane's head, this lane's share of the weights
 
             for (int t = 0; t < my_tiles; ++t) {
                 top_up();
-                // tile t is complete once at most the loads of the tiles fetched after it are outstanding
-                const int later = ahead - 1;
-                if (later >= 3) wait_vmcnt<3 * LOADS>();
-                else if (later == 2) wait_vmcnt<2 * LOADS>();
-                else if (later == 1) wait_vmcnt<LOADS>();
-                else wait_vmcnt<0>();
-                static_assert(kStages <= 4, "the wait ladder above handles at most three later tiles");
+                // Tile t has landed once no more is outstanding than was requested after it: the later
+                // tiles in the ring and their query blocks.
+                wait_all_but<LOADS, QL>(ahead - 1, __builtin_popcount(q_mask & ~(1u << c_stage)));
+                q_mask &= ~(1u << c_stage);
+                if (t == 0) {
+                    // q as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8].  Heads
+                    // >= G repeat head G-1: their columns of the products are computed and never stored.
+                    const char *qsrc = q_ring + c_stage * QBUF + min(l16, G - 1) * ROWB + lq * 16;
+#pragma unroll
+                    for (int s = 0; s < NSL; ++s)
+                        qb[s] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(qsrc + s * 64));
+                }
 
-                const char *kst = ring + c_stage * STAGEB;
-                const char *vst = kst + TILEB;
-                const int tok0 = (wave + t * kWaves) * kTok;
-                const int nv = min(kTok, n - tok0);
+                // ---- every LDS read of the tile, issued together -----------------------------------
+                const char *st = ring + c_stage * STAGEB;
+                uint4 kw[NSL];
+                i16x4_t vt[NDB];
+#pragma unroll
+                for (int s = 0; s < NSL; ++s) kw[s] = *reinterpret_cast<const uint4 *>(st + k_rd[s]);
+#pragma unroll
+                for (int nb_ = 0; nb_ < NDB; ++nb_)
+                    vt[nb_] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(st + v_rd[nb_]));
 
-                // ---- scores: S^T[token 4 lq + i][head l16] -----------------------------------------
+                // ---- scores: S^T[token 4 lq + i][head l16], in log2 units --------------------------
                 f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < NSL; ++s) {
-                    const int piece = 4 * s + lq;
-                    const uint4 kw = *reinterpret_cast<const uint4 *>(kst + l16 * ROWB + ((piece ^ (l16 % PPR)) * 16));
-                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw), qb[s], sacc, 0, 0, 0);
+                for (int s = 0; s < NSL; ++s)
+                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw[s]), qb[s], sacc, 0, 0, 0);
+                const int nv = n - (wave + t * kWaves) * kTok;     // valid tokens of the tile if below kTok
+                float sv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * a.scale_log2;
+                if (nv < kTok) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (4 * lq + i >= nv) sv[i] = -INFINITY;
                 }
 
-                // ---- online softmax, all in this lane's head ----------------------------------------
-                float sv[4];
-                float mx = -INFINITY;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    sv[i] = (4 * lq + i) < nv ? sacc[i] * a.scale_log2 : -INFINITY;
-                    mx = fmaxf(mx, sv[i]);
-                }
-                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first tile
-                float p[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
-                const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
-                // the sum uses the rounded weights, so out is an exact convex combination of V rows
-                float psum = 0.f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) psum += static_cast<float>(pb[i]);
-                l_run = l_run * alpha + psum;
-                m_run = m_new;
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+                // ---- raise the reference maximum if some score is far above it (always on the first tile)
+                float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+                if (__builtin_amdgcn_ballot_w64(mx > m_run + kBump) != 0) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    const float m_new = fmaxf(m_run, mx);
+                    const float alpha = m_new == m_run ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
+                    l_run *= alpha;
 #pragma unroll
                     for (int nb_ = 0; nb_ < NDB; ++nb_)
 #pragma unroll
                         for (int i = 0; i < 4; ++i) o[nb_][i] *= alpha;
+                    m_run = m_new;
                 }
 
-                // ---- O^T[d][head] += V^T P: transposing LDS read gives V[token 4 lq + i][16 nb + l16] ----
-                const int vrow = 4 * lq + (l16 >> 2);     // row this lane addresses for the transposing read
-                const int vsub = l16 & 3;                 // which 4 d's (8 bytes) of the 16-wide block
+                // ---- weights, rounded to bf16; their sum uses the rounded values, so out is an exact
+                //      convex combination of V rows -------------------------------------------------
+                float p[4];
 #pragma unroll
-                for (int nb_ = 0; nb_ < NDB; ++nb_) {
-                    const int piece = 2 * nb_ + (vsub >> 1);
-                    const char *src = vst + vrow * ROWB + ((piece ^ ((2 * vrow) % PPR)) * 16) + (vsub & 1) * 8;
-                    i16x4_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(src));
-                    if (nv < kTok) {     // rows past the end hold a re-read row: keep inf/NaN in it from leaking in
+                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_run);
+                const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (4 * lq + i >= nv) vt[i] = 0;
-                    }
-                    o[nb_] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, __builtin_bit_cast(i16x4_t, pb), o[nb_], 0, 0, 0);
-                }
-                c_stage = (c_stage + 1) % kStages;
+                for (int i = 0; i < 4; ++i) l_run += static_cast<float>(pb[i]);
+
+                // ---- O^T[d][head] += V^T P ---------------------------------------------------------
+#pragma unroll
+                for (int nb_ = 0; nb_ < NDB; ++nb_)
+                    o[nb_] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[nb_], __builtin_bit_cast(i16x4_t, pb), o[nb_], 0, 0, 0);
+                c_stage = c_stage + 1 == kStages ? 0 : c_stage + 1;
                 --ahead;
             }
 

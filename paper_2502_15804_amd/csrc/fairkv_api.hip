@@ -125,12 +125,13 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     for (int32_t j = 0; j <= n_slots; ++j) a.slot_ptr[j] = slot_ptr[j];
     for (int32_t j = 0; j < n_slots; ++j) {
         a.first_row[j] = 0;
-        a.first_n[j] = 0;
+        a.first_np[j] = 0;
         if (slot_ptr[j] == slot_ptr[j + 1]) continue;
         const fairkv_item &it = items_host[slot_ptr[j]];
-        if (it.row + it.tok_count > static_cast<int64_t>(UINT32_MAX)) continue;   // does not fit: normal start
+        const int64_t pair = static_cast<int64_t>(it.b) * Hkv + it.h;
+        if (it.row > static_cast<int64_t>(UINT32_MAX) || pair >= (1 << 24)) continue;   // does not fit: normal start
         a.first_row[j] = static_cast<uint32_t>(it.row);
-        a.first_n[j] = static_cast<uint32_t>(it.tok_count);
+        a.first_np[j] = (static_cast<uint32_t>(pair) << 8) | static_cast<uint32_t>(it.tok_count < kEarlyTok ? it.tok_count : kEarlyTok);
     }
     a.arrivals = reinterpret_cast<int32_t *>(ws);
     ws += align256(static_cast<size_t>(B) * Hkv * sizeof(int32_t));
