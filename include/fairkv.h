@@ -100,8 +100,8 @@ typedef struct {
 } fairkv_plan_summary;
 
 /* Defaults: n_slots = n_compute_units, tile 16, min_chunk 32, max_split 256, oversub 2,
- * overhead_tokens 256 (measured on MI355X: an extra item in a slot costs about as much as
- * streaming 200-300 tokens), policy FAIR.  n_compute_units must be >= 1. */
+ * overhead_tokens 128 (measured on MI355X: an extra item in a slot costs about as much as
+ * streaming 100-150 tokens), policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
 /*
@@ -158,7 +158,7 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * items of a cut pair leave partial results in the workspace and the one that finishes last
  * combines them (log-sum-exp merge), so no second launch is needed.
  *
- * q          device [B][Hq][D], element type in_dtype
+ * q          device [B][Hq][D], element type in_dtype, 16-byte aligned
  * k, v       device [n_rows][D], element type in_dtype, 16-byte aligned
  * items      device [n_items]: the items of a plan made by fairkv_plan from this cache's len
  *            and off, copied to the device by the caller.  The kernels read exactly the rows
@@ -173,7 +173,7 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * workspace  device, at least fairkv_workspace_bytes(n_parts, B*Hkv, G, D) bytes, 16-byte
  *            aligned, zero-filled before its first use (see fairkv_workspace_bytes)
  * out        device [B][Hq][D], element type out_dtype (FAIRKV_F32, or FAIRKV_BF16 rounded
- *            to nearest even)
+ *            to nearest even), 16-byte aligned
  * lse        device [B][Hq] float, or NULL
  * scale      multiplies the scores (1/sqrt(D) in the usual models)
  * hip_stream a hipStream_t (NULL = the default stream)

@@ -49,7 +49,7 @@ class Params:
     min_chunk: int = 32
     max_split: int = 256
     oversub: int = 2
-    overhead_tokens: int = 256
+    overhead_tokens: int = 128
     policy: int = POLICY_FAIR
 
 

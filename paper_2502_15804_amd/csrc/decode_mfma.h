@@ -43,7 +43,7 @@ typedef __attribute__((ext_vector_type(4))) short i16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kTok = 16;      // tokens per tile (the M of the score MFMA, the K of the PV MFMA)
-constexpr int kStages = 3;    // tiles per wave resident in LDS: one being consumed, the others in flight
+constexpr int kStages = 2;    // tiles per wave resident in LDS: one being consumed, the others in flight (3 measured no faster)
 constexpr float kBump = 8.f;  // log2 units a score may exceed the reference maximum before it is raised
 
 #define FAIRKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     __shared__ __attribute__((aligned(1024))) fairkv_item raw[kTable];        // items as fetched
     __shared__ __attribute__((aligned(16))) ItemSlot table[kTable];           // items as checked
     __shared__ __attribute__((aligned(16))) float st_o[kWaves * G * D];
-    __shared__ float st_ml[kWaves * G * 2];
+    __shared__ __attribute__((aligned(16))) float st_ml[kWaves * G * 2];
     __shared__ PendingParts<D, G> pend;
     int n_pend = 0;
 

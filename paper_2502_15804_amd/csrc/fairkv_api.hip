@@ -109,7 +109,7 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     const int G = Hq / Hkv;
     if (D != 64 && D != 128) return FAIRKV_EUNSUPPORTED;
     if (G != 1 && G != 2 && G != 4 && G != 8) return FAIRKV_EUNSUPPORTED;
-    if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items)) return FAIRKV_EINVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items) || !aligned16(out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, G, D);
     if (!workspace || workspace_bytes < need) return FAIRKV_EWORKSPACE;
