@@ -42,6 +42,10 @@ def parse():
                     help="instead of the benchmark: decode latency of one Llama-70B-shaped layer against batch size "
                          "and against a uniform per-head budget (the paper's Section 3.2 / Figure 2 experiment), "
                          "with least-squares lines L = alpha*B + beta and L = gamma*C + delta")
+    ap.add_argument("--placement-table", action="store_true",
+                    help="instead of the benchmark: place the KV heads of one mistral24b-shaped layer on 2, 4 and 8 "
+                         "GPUs (static, Best-effort Assignment, Fair-Copying) with fairkv_place and time every GPU's "
+                         "share on this GPU (the paper's Section 4.3; busy rate and step time per scheme)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -162,6 +166,88 @@ def spot_check(rot, n_layers=2, n_samples=48):
     return worst
 
 
+def graph_time_us(layers, bytes_layer):
+    """Microseconds per launch of a rotation of DecodeLayer objects, replayed as one HIP graph."""
+    import torch
+    n_buf = len(layers)
+    g = torch.cuda.CUDAGraph()
+    for l in layers:
+        l.run()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        for l in layers:
+            l.run()
+    reps = max(3, int(2e-3 / (n_buf * max(bytes_layer, 1) / 4e12)))
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return 1e3 * e0.elapsed_time(e1) / (reps * n_buf)
+
+
+def placement_table(seed=0, name="mistral24b"):
+    """Section 4.3 / Section 5 of the paper at kernel level on this GPU: the KV heads of one layer are placed
+    on tp GPUs by static head allocation, by Best-effort Assignment (no copies) and by Fair-Copying with up to
+    CH extra copies (fairkv_place); every GPU's share then runs through fairkv_plan + fairkv_decode_attn here,
+    one share at a time, and the step time of the group is the slowest share's.  Busy rate = mean / max."""
+    import numpy as np
+    import workloads as W
+    import paper_2502_15804_amd as F
+    from paper_2502_15804_amd.runtime import DecodeLayer, gpu_share
+
+    w0 = W.WORKLOADS[name]
+    # four layers' budgets stacked as batch rows: B = 128, so that a GPU's share of one layer is tens of MB
+    lens = np.concatenate([W.lens(name, seed=seed, layer=i) for i in range(4)], axis=0)
+    w = W.Workload(name, lens.shape[0], w0.Hq, w0.Hkv, w0.D, w0.dtype, 1, w0.tol, "")
+    Wh = lens.astype(np.int64).sum(axis=0)
+    rows = []
+
+    def run_scheme(tp, label, shares, eff_model):
+        times = []
+        for gpu in range(tp):
+            heads, ll = gpu_share(lens, shares, gpu)
+            if not heads:
+                times.append(0.0)
+                continue
+            wl = W.Workload("share", w.B, len(heads) * w.G, len(heads), w.D, w.dtype, 1, w.tol, "")
+            off, total = W.packed_offsets(ll)
+            bytes_layer = W.algorithmic_bytes(wl, ll)
+            n_buf = max(2, min(48, int(1.0e9 // max(bytes_layer, 1)) + 1))
+            layers = []
+            for i in range(n_buf):
+                q, k, v = W.make_qkv(wl, max(total, 1), seed=seed, layer=i, device="cuda")
+                layers.append(DecodeLayer(q, k, v, off, ll, wl.scale, want_lse=False))
+            times.append(graph_time_us(layers, bytes_layer))
+            del layers
+        mx = max(times)
+        rows.append({"tp": tp, "scheme": label, "copies": int(len(shares) - len(Wh)),
+                     "efficiency_model": round(eff_model, 4), "busy_rate_measured": round(float(np.mean(times)) / mx, 4),
+                     "step_us": round(mx, 2), "per_gpu_us": [round(t, 2) for t in times]})
+
+    for tp in (2, 4, 8):
+        per = len(Wh) // tp
+        sha = np.zeros(len(Wh), dtype=F.SHARE_DTYPE)
+        for h in range(len(Wh)):
+            sha[h] = (h, h // per, 0, 1, 0, w.B)
+        loads = [int(Wh[j * per:(j + 1) * per].sum()) for j in range(tp)]
+        run_scheme(tp, "static", sha, sum(loads) / (tp * max(loads)))
+        for ch in (0, 1, 2, 4):
+            pl = F.fairkv_place(Wh, w.B, tp, ch, 4 if ch else 1)
+            run_scheme(tp, "best-effort" if ch == 0 else f"fair-copying CH<={ch}", pl.shares, pl.summary.efficiency)
+    for tp in (2, 4, 8):
+        base = [r for r in rows if r["tp"] == tp and r["scheme"] == "static"][0]["step_us"]
+        for r in rows:
+            if r["tp"] == tp:
+                r["speedup_vs_static"] = round(base / r["step_us"], 3)
+    return {"experiment": "head placement over a tensor-parallel group, each GPU's share timed on this GPU "
+                          "(paper Section 4.3 and Figure 4 / Table 2 analogue)",
+            "profile": f"{name} recipe, B={w.B}: summed budgets per KV head = {Wh.tolist()}", "rows": rows}
+
+
 def latency_model(seed=0):
     """Section 3.2 of the paper on this GPU: one layer (64 query / 8 KV heads, D=128, bf16), every head with the
     same budget C, batch B; time per decode step through the whole path (plan resident, one launch)."""
@@ -183,25 +269,9 @@ def latency_model(seed=0):
             for i in range(n_buf):
                 q, k, v = W.make_qkv(w, total, seed=seed, layer=i, device="cuda")
                 layers.append(DecodeLayer(q, k, v, off, lens, w.scale, want_lse=False))
-            g = torch.cuda.CUDAGraph()
-            for l in layers:
-                l.run()
-            torch.cuda.synchronize()
-            with torch.cuda.graph(g):
-                for l in layers:
-                    l.run()
-            reps = max(3, int(2e-3 / (n_buf * bytes_layer / 4e12)))
-            g.replay()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                g.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            us = 1e3 * e0.elapsed_time(e1) / (reps * n_buf)
+            us = graph_time_us(layers, bytes_layer)
             table[(B, C)] = (us, bytes_layer / us / 1e3)
-            del layers, g
+            del layers
             torch.cuda.empty_cache()
 
     def fit(xs, ys):
@@ -273,6 +343,9 @@ def main():
     F.lib()
     if a.latency_model:
         print(json.dumps(latency_model(a.seed)))
+        return
+    if a.placement_table:
+        print(json.dumps(placement_table(a.seed)))
         return
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers

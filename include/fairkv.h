@@ -42,7 +42,7 @@ extern "C" {
 typedef enum {
     FAIRKV_OK = 0,
     FAIRKV_EINVAL = -1,       /* null pointer, non-positive size, bad parameter combination */
-    FAIRKV_ECAP = -2,         /* caller's items array is too small; summary.n_items says how big */
+    FAIRKV_ECAP = -2,         /* caller's output array is too small; the summary says how big */
     FAIRKV_EWORKSPACE = -3,   /* workspace smaller than fairkv_workspace_bytes() */
     FAIRKV_EUNSUPPORTED = -4, /* element type / head_dim / group size without a kernel */
     FAIRKV_EHIP = -5          /* a HIP call failed; the HIP error is left for hipGetLastError */
@@ -189,6 +189,63 @@ int fairkv_decode_attn(const void *q, const void *k, const void *v,
                        void *out, float *lse,
                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
                        int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream);
+
+/* ---- placement over the GPUs of a tensor-parallel group (Section 4.3, Algorithms 1 and 2) -------
+ *
+ * Host only.  Which GPU holds which attention head of one layer, and which heads are replicated
+ * so that their copies share the batch rows (Fair-Copying); with max_extra = 0 it is the
+ * Best-effort Assignment (heads permuted over GPUs, no copies).  A copy of a head with c copies
+ * weighs W / c (Algorithm 2's adjusted weights); the scheme kept is the first one, in the order of
+ * the paper's two algorithms, with the smallest difference between the heaviest and the lightest
+ * GPU (Algorithm 2's criterion).  Appendix A: every head is placed (eq. 2), at most max_copies
+ * copies per head (eq. 3), efficiency = mean load / largest load (eq. 5).
+ *
+ * Readings: the extra copies of a scheme, sum over heads of (copies - 1), are at most max_extra
+ * (Algorithm 1 declares such a bound and never uses it); the copies of a head sit on different
+ * GPUs; GPUs may hold different numbers of heads; an idle GPU weighs 0; schemes are walked head
+ * by head with 1 copy first, then 2, 3, ..., and splits in lexicographic order of the GPU of
+ * (head 0 copy 0, head 0 copy 1, ..., head 1 copy 0, ...).
+ *
+ * FAIRKV_PLACE_EXACT walks all schemes (exponential: meant for the paper's handful of heads);
+ * FAIRKV_PLACE_GREEDY places copies longest first on the least loaded GPU that does not hold
+ * the head yet, then up to max_extra times gives one more copy to the heaviest copy on the
+ * most loaded GPU while that lowers the largest load; FAIRKV_PLACE_AUTO is EXACT while
+ * n_heads + max_extra <= 12, else GREEDY. */
+enum { FAIRKV_PLACE_AUTO = 0, FAIRKV_PLACE_EXACT = 1, FAIRKV_PLACE_GREEDY = 2 };
+
+typedef struct {
+    int32_t tp;          /* GPUs of the group, >= 1 */
+    int32_t max_extra;   /* m: extra copies in total, >= 0 */
+    int32_t max_copies;  /* R_max of eq. 3: copies per head, 1..8 (and never more than tp) */
+    int32_t mode;        /* FAIRKV_PLACE_* */
+} fairkv_place_params;
+
+/* One copy of a head: GPU `gpu` serves batch rows [row_begin, row_end) of head `head`.  The
+ * copies of a head are numbered by ascending GPU and share the B rows contiguously; with c
+ * copies the first B mod c of them take ceil(B / c) rows. */
+typedef struct {
+    int32_t head, gpu, copy, n_copies, row_begin, row_end;
+} fairkv_share; /* 24 bytes */
+
+typedef struct {
+    int64_t den;           /* loads are in units of 1/den tokens, den = lcm(1..max_copies) */
+    int64_t delta_num;     /* heaviest minus lightest GPU */
+    int64_t max_load_num;
+    int64_t min_load_num;
+    double efficiency;     /* eq. 5 */
+    int32_t n_shares;      /* copies in the scheme (also when they did not fit shares_cap) */
+    int32_t exact;         /* 1: exhaustive walk, 0: greedy */
+} fairkv_place_summary;
+
+/* W         host [n_heads]: weight of every head (tokens it keeps, summed over the batch), 0..2^40
+ * B         batch rows to share among the copies of a head, >= 1
+ * shares    host [shares_cap], out, ordered by (head, copy); may be NULL iff shares_cap == 0
+ * gpu_load  host [tp] or NULL, out: load of every GPU in units of 1/den
+ * summary   host, out, required
+ * Returns FAIRKV_ECAP (summary and gpu_load filled, no share written) when the scheme has more
+ * copies than shares_cap; n_heads + max_extra always suffices. */
+int fairkv_place(const int64_t *W, int32_t n_heads, int32_t B, const fairkv_place_params *p,
+                 fairkv_share *shares, int32_t shares_cap, int64_t *gpu_load, fairkv_place_summary *summary);
 
 const char *fairkv_strerror(int code);
 int fairkv_version(void);

@@ -20,8 +20,10 @@ FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, F
 FAIRKV_BF16, FAIRKV_F32 = 0, 1
 FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
+FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
+
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
-           "fairkv_strerror", "fairkv_version")
+           "fairkv_place", "fairkv_strerror", "fairkv_version")
 
 
 class fairkv_item(ctypes.Structure):
@@ -38,6 +40,23 @@ class fairkv_plan_summary(ctypes.Structure):
     _fields_ = [("total_tokens", ctypes.c_int64), ("max_slot_load", ctypes.c_int64),
                 ("min_slot_load", ctypes.c_int64), ("n_items", ctypes.c_int32), ("n_parts", ctypes.c_int32)]
 
+
+class fairkv_place_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("tp", "max_extra", "max_copies", "mode")]
+
+
+class fairkv_share(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("head", "gpu", "copy", "n_copies", "row_begin", "row_end")]
+
+
+class fairkv_place_summary(ctypes.Structure):
+    _fields_ = [("den", ctypes.c_int64), ("delta_num", ctypes.c_int64), ("max_load_num", ctypes.c_int64),
+                ("min_load_num", ctypes.c_int64), ("efficiency", ctypes.c_double), ("n_shares", ctypes.c_int32),
+                ("exact", ctypes.c_int32)]
+
+
+SHARE_DTYPE = np.dtype([(n, np.int32) for n, _ in fairkv_share._fields_])
+assert SHARE_DTYPE.itemsize == ctypes.sizeof(fairkv_share) == 24
 
 ITEM_DTYPE = np.dtype([("row", np.int64)] + [(n, np.int32) for n, _ in fairkv_item._fields_[1:]])
 assert ITEM_DTYPE.itemsize == ctypes.sizeof(fairkv_item) == 32
@@ -71,6 +90,9 @@ def lib() -> ctypes.CDLL:
         L.fairkv_decode_attn.restype = ctypes.c_int
         L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
                                          i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.fairkv_place.restype = ctypes.c_int
+        L.fairkv_place.argtypes = [vp, i32, i32, ctypes.POINTER(fairkv_place_params), vp, i32, vp,
+                                   ctypes.POINTER(fairkv_place_summary)]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -147,6 +169,28 @@ def fairkv_plan(lens, off, B: int, Hkv: int, params: fairkv_plan_params) -> Plan
         if rc != FAIRKV_OK:
             raise FairKVError(rc, "fairkv_plan")
     return Plan(items, slot_ptr, part_base, summary, params)
+
+
+@dataclass
+class Placement:
+    """Host-side result of fairkv_place."""
+    shares: np.ndarray       # structured array of fairkv_share, ordered by (head, copy)
+    gpu_load: np.ndarray     # int64 [tp], in units of 1/summary.den tokens
+    summary: fairkv_place_summary
+    params: fairkv_place_params
+
+
+def fairkv_place(W, B: int, tp: int, max_extra: int = 0, max_copies: int = 1, mode: int = FAIRKV_PLACE_AUTO) -> Placement:
+    W = np.ascontiguousarray(np.asarray(W).reshape(-1), dtype=np.int64)
+    p = fairkv_place_params(int(tp), int(max_extra), int(max_copies), int(mode))
+    s = fairkv_place_summary()
+    shares = np.zeros(W.size + max(int(max_extra), 0), dtype=SHARE_DTYPE)
+    load = np.zeros(max(int(tp), 1), dtype=np.int64)
+    rc = lib().fairkv_place(W.ctypes.data, W.size, int(B), ctypes.byref(p), shares.ctypes.data, shares.size,
+                            load.ctypes.data, ctypes.byref(s))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_place")
+    return Placement(shares[:s.n_shares].copy(), load, s, p)
 
 
 def fairkv_workspace_bytes(n_parts: int, n_pairs: int, G: int, D: int) -> int:

@@ -215,7 +215,7 @@ extern "C" const char *fairkv_strerror(int code)
     switch (code) {
     case FAIRKV_OK: return "ok";
     case FAIRKV_EINVAL: return "invalid argument";
-    case FAIRKV_ECAP: return "items array too small";
+    case FAIRKV_ECAP: return "output array too small";
     case FAIRKV_EWORKSPACE: return "workspace too small";
     case FAIRKV_EUNSUPPORTED: return "unsupported element type, head_dim or group size";
     case FAIRKV_EHIP: return "HIP call failed";

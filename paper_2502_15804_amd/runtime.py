@@ -50,3 +50,21 @@ class DecodeLayer:
         fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.items, self.plan.slot_ptr, self.plan.n_parts,
                            self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
         return self.out, self.lse
+
+
+def gpu_share(lens, shares, gpu):
+    """One GPU's part of a placement made by fairkv_place: (heads, len_local).
+
+    heads      the KV heads this GPU holds, ascending
+    len_local  int32 [B][len(heads)]: len[b][head] for the batch rows this GPU serves of that
+               head, 0 for the rows another copy serves (such pairs get empty items, no K/V).
+    The GPU then runs fairkv_plan + fairkv_decode_attn on len_local like on any other cache.
+    """
+    lens = np.asarray(lens)
+    mine = [s for s in shares if int(s["gpu"]) == int(gpu)]
+    heads = sorted(int(s["head"]) for s in mine)
+    out = np.zeros((lens.shape[0], len(heads)), dtype=np.int32)
+    for s in mine:
+        col = heads.index(int(s["head"]))
+        out[int(s["row_begin"]):int(s["row_end"]), col] = lens[int(s["row_begin"]):int(s["row_end"]), int(s["head"])]
+    return heads, out
