@@ -180,3 +180,22 @@ def to_numpy_bits(t):
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16)
     return t.numpy()
+
+
+def keep_lists(len_bh: np.ndarray, T: int, seed: int = 0, recent: int = 32):
+    """Which tokens of a dense cache of T tokens every pair keeps: (keep_ptr int64 [n_pairs+1],
+    keep_t int32 [total]), ascending inside a pair.  Shaped like the output of a per-head
+    compressor: the most recent `recent` tokens are always kept, the rest of the budget is
+    scattered over the earlier positions.  Selection itself is not part of this build."""
+    flat = np.asarray(len_bh).reshape(-1).astype(np.int64)
+    if flat.size and flat.max() > T:
+        raise ValueError("a pair cannot keep more tokens than the dense cache has")
+    keep_ptr = np.concatenate([[0], np.cumsum(flat)]).astype(np.int64)
+    keep_t = np.empty(int(keep_ptr[-1]), dtype=np.int32)
+    rng = np.random.default_rng([seed, 0x6b656570])
+    for p, n in enumerate(flat):
+        n = int(n)
+        tail = min(n, recent)
+        old = rng.choice(T - tail, size=n - tail, replace=False) if n > tail else np.empty(0, np.int64)
+        keep_t[keep_ptr[p]:keep_ptr[p + 1]] = np.concatenate([np.sort(old), np.arange(T - tail, T)]).astype(np.int32)
+    return keep_ptr, keep_t
