@@ -247,6 +247,43 @@ typedef struct {
 int fairkv_place(const int64_t *W, int32_t n_heads, int32_t B, const fairkv_place_params *p,
                  fairkv_share *shares, int32_t shares_cap, int64_t *gpu_load, fairkv_place_summary *summary);
 
+/* ---- building and growing the packed cache (the step before the path) ---------------------------
+ *
+ * fairkv_pack gathers the tokens a per-head compressor kept (Section 2: which entries a method
+ * retains per head is its own business) out of a dense cache into the packed layout: for pair
+ * p = b*Hkv + h and i < len, packed row off[p] + i = dense row keep_t[keep_ptr[p] + i] of
+ * k_dense[b][h].  The rows to move are named by a work list in the format of fairkv_plan (made
+ * from the same len and off: an item is a run of tok_count packed rows of pair (b, h) starting
+ * at row; chunk fields are ignored), so that a ragged cache is gathered by evenly loaded
+ * workgroups, one per slot.  Rows of no pair are left untouched.
+ *
+ * All pointers are DEVICE pointers.  k_dense, v_dense [B][Hkv][T][D] and k_out, v_out
+ * [n_rows][D] of element type dtype, 16-byte aligned; keep_ptr int64 [B*Hkv+1]; keep_t int32;
+ * off int64 [B*Hkv]; items [slot_ptr[n_slots]], slot_ptr int32 [n_slots+1]; bad: int32 counter or
+ * NULL, incremented for every item or row that points outside its arrays (such rows are skipped,
+ * nothing out of bounds is touched).  Supported: D * sizeof(element) in {128, 256, 512}.
+ * Enqueues one kernel on hip_stream; no synchronisation. */
+int fairkv_pack(const void *k_dense, const void *v_dense, int32_t B, int32_t Hkv, int32_t T, int32_t D,
+                int32_t dtype, const int64_t *keep_ptr, const int32_t *keep_t, const int64_t *off,
+                const fairkv_item *items, const int32_t *slot_ptr, int32_t n_slots, void *k_out, void *v_out,
+                int64_t n_rows, int32_t *bad, void *hip_stream);
+
+/* fairkv_append puts a decode step's new K and V row of every pair (k_new, v_new [B][Hkv][D])
+ * behind the pair's last row, row off[p] + len[p], and adds one to len[p]; a pair with
+ * len[p] >= cap[p] (its reserved rows are used up) is left alone and counted in *full.  All
+ * pointers are DEVICE pointers; len is updated in place.  The caller re-plans (or grows the last
+ * chunk of every pair in its plan) from the new lengths.  Enqueues one kernel; no synchronisation. */
+int fairkv_append(const void *k_new, const void *v_new, int32_t B, int32_t Hkv, int32_t D, int32_t dtype,
+                  const int64_t *off, int32_t *len, const int32_t *cap, void *k, void *v, int64_t n_rows,
+                  int32_t *full, void *hip_stream);
+
+/* Host mirror of fairkv_append for a plan that stays in use: the last chunk of every pair whose
+ * len[p] < cap[p] covers one more row (tok_count + 1) and len[p] grows by one; pairs at capacity
+ * are left alone.  items, len (in/out) and cap are HOST arrays; items must be a whole plan (one
+ * last chunk per pair).  The plan stays valid and drifts from balance by at most one row per pair
+ * and step; re-plan with fairkv_plan every few hundred steps. */
+int fairkv_plan_grow(fairkv_item *items, int32_t n_items, int32_t B, int32_t Hkv, int32_t *len, const int32_t *cap);
+
 const char *fairkv_strerror(int code);
 int fairkv_version(void);
 

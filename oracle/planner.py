@@ -217,6 +217,19 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
     return items, slot_ptr, part_base, summary
 
 
+def grow(items, lens, cap, Hkv: int):
+    """A decode step appended one row to every pair below its capacity: the pair's last chunk
+    covers it.  Returns the new item list; lens is updated in place."""
+    out = []
+    for it in items:
+        pair = it.b * Hkv + it.h
+        if it.chunk == it.n_chunks - 1 and lens[pair] < cap[pair]:
+            lens[pair] += 1
+            it = Item(it.row, it.tok_count + 1, it.b, it.h, it.chunk, it.n_chunks, it.part)
+        out.append(it)
+    return out
+
+
 # ---- figures of merit, straight from the paper's definitions ------------------------
 def slot_loads(items, slot_ptr, overhead_tokens: int):
     return [sum(it.tok_count + overhead_tokens for it in items[slot_ptr[j]:slot_ptr[j + 1]])

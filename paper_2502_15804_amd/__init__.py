@@ -23,7 +23,7 @@ FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_F
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
-           "fairkv_place", "fairkv_strerror", "fairkv_version")
+           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_strerror", "fairkv_version")
 
 
 class fairkv_item(ctypes.Structure):
@@ -93,6 +93,12 @@ def lib() -> ctypes.CDLL:
         L.fairkv_place.restype = ctypes.c_int
         L.fairkv_place.argtypes = [vp, i32, i32, ctypes.POINTER(fairkv_place_params), vp, i32, vp,
                                    ctypes.POINTER(fairkv_place_summary)]
+        L.fairkv_pack.restype = ctypes.c_int
+        L.fairkv_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_int64, vp, vp]
+        L.fairkv_append.restype = ctypes.c_int
+        L.fairkv_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_int64, vp, vp]
+        L.fairkv_plan_grow.restype = ctypes.c_int
+        L.fairkv_plan_grow.argtypes = [vp, i32, i32, i32, vp, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -244,3 +250,74 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
         ctypes.c_void_p(stream.cuda_stream))
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_decode_attn")
+
+
+def _dtype_code(t):
+    import torch
+    return {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}[t.dtype]
+
+
+def _check_dev(**tensors):
+    for name, t in tensors.items():
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous device tensor")
+
+
+def fairkv_pack(k_dense, v_dense, keep_ptr, keep_t, off, items, slot_ptr, k_out, v_out, bad=None, stream=None):
+    """Enqueue the gather of the kept rows.  All arguments are device tensors: k_dense, v_dense
+    [B][Hkv][T][D]; keep_ptr int64 [B*Hkv+1]; keep_t int32; off int64 [B*Hkv]; items uint8 view of a
+    plan's item array; slot_ptr int32 [n_slots+1]; k_out, v_out [n_rows][D]; bad int32 [1] or None."""
+    import torch
+
+    B, Hkv, T, D = k_dense.shape
+    _check_dev(k_dense=k_dense, v_dense=v_dense, keep_ptr=keep_ptr, keep_t=keep_t, off=off, items=items,
+               slot_ptr=slot_ptr, k_out=k_out, v_out=v_out, bad=bad)
+    if (v_dense.shape != k_dense.shape or k_out.shape != v_out.shape or k_out.shape[1] != D
+            or k_out.dtype != k_dense.dtype or v_out.dtype != k_dense.dtype or v_dense.dtype != k_dense.dtype):
+        raise ValueError("shape or dtype mismatch")
+    if (keep_ptr.dtype != torch.int64 or off.dtype != torch.int64 or keep_t.dtype != torch.int32
+            or slot_ptr.dtype != torch.int32 or keep_ptr.numel() != B * Hkv + 1 or off.numel() != B * Hkv
+            or (bad is not None and bad.dtype != torch.int32)):
+        raise TypeError("keep_ptr/off must be int64, keep_t/slot_ptr/bad int32, sized for B*Hkv pairs")
+    if stream is None:
+        stream = torch.cuda.current_stream(k_dense.device)
+    rc = lib().fairkv_pack(_ptr(k_dense), _ptr(v_dense), B, Hkv, T, D, _dtype_code(k_dense), _ptr(keep_ptr),
+                           _ptr(keep_t), _ptr(off), _ptr(items), _ptr(slot_ptr), slot_ptr.numel() - 1, _ptr(k_out),
+                           _ptr(v_out), k_out.shape[0], _ptr(bad), ctypes.c_void_p(stream.cuda_stream))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_pack")
+
+
+def fairkv_append(k_new, v_new, off, lens, cap, k, v, full=None, stream=None):
+    """Enqueue the append of one new row per pair.  Device tensors: k_new, v_new [B][Hkv][D]; off int64,
+    lens int32 (updated in place), cap int32, all [B*Hkv]; k, v packed [n_rows][D]; full int32 [1] or None."""
+    import torch
+
+    B, Hkv, D = k_new.shape
+    _check_dev(k_new=k_new, v_new=v_new, off=off, lens=lens, cap=cap, k=k, v=v, full=full)
+    if (v_new.shape != k_new.shape or k.shape != v.shape or k.shape[1] != D or k.dtype != k_new.dtype
+            or v.dtype != k_new.dtype or v_new.dtype != k_new.dtype):
+        raise ValueError("shape or dtype mismatch")
+    if (off.dtype != torch.int64 or lens.dtype != torch.int32 or cap.dtype != torch.int32
+            or off.numel() != B * Hkv or lens.numel() != B * Hkv or cap.numel() != B * Hkv
+            or (full is not None and full.dtype != torch.int32)):
+        raise TypeError("off must be int64, lens/cap/full int32, sized for B*Hkv pairs")
+    if stream is None:
+        stream = torch.cuda.current_stream(k_new.device)
+    rc = lib().fairkv_append(_ptr(k_new), _ptr(v_new), B, Hkv, D, _dtype_code(k_new), _ptr(off), _ptr(lens), _ptr(cap),
+                             _ptr(k), _ptr(v), k.shape[0], _ptr(full), ctypes.c_void_p(stream.cuda_stream))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_append")
+
+
+def fairkv_plan_grow(items: np.ndarray, B: int, Hkv: int, lens: np.ndarray, cap: np.ndarray) -> None:
+    """Host arrays, updated in place: items (a whole plan, ITEM_DTYPE), lens int32 [B*Hkv]; cap int32 [B*Hkv]."""
+    if items.dtype != ITEM_DTYPE or not items.flags.c_contiguous:
+        raise TypeError("items must be a contiguous fairkv_item array")
+    if lens.dtype != np.int32 or cap.dtype != np.int32 or not lens.flags.c_contiguous or not cap.flags.c_contiguous:
+        raise TypeError("lens and cap must be contiguous int32 arrays")
+    if lens.size != B * Hkv or cap.size != B * Hkv:
+        raise ValueError("lens and cap must have B*Hkv entries")
+    rc = lib().fairkv_plan_grow(items.ctypes.data, items.size, int(B), int(Hkv), lens.ctypes.data, cap.ctypes.data)
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_plan_grow")

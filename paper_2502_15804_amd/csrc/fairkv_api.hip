@@ -15,6 +15,7 @@
 
 #include "decode_mfma.h"
 #include "decode_valu.h"
+#include "pack.h"
 #include "fairkv.h"
 
 namespace {
@@ -155,4 +156,61 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     else
         e = D == 128 ? launch_valu<FAIRKV_F32, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_F32, 64>(G, a, n_slots, st);
     return e == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
+}
+
+// ---- packing and appending ------------------------------------------------------------------------
+namespace {
+int row_bytes_of(int32_t D, int32_t dtype)
+{
+    if (dtype != FAIRKV_BF16 && dtype != FAIRKV_F32) return 0;
+    const int64_t rb = static_cast<int64_t>(D) * (dtype == FAIRKV_BF16 ? 2 : 4);
+    return (rb == 128 || rb == 256 || rb == 512) ? static_cast<int>(rb) : 0;
+}
+}  // namespace
+
+extern "C" int fairkv_pack(const void *k_dense, const void *v_dense, int32_t B, int32_t Hkv, int32_t T, int32_t D,
+                           int32_t dtype, const int64_t *keep_ptr, const int32_t *keep_t, const int64_t *off,
+                           const fairkv_item *items, const int32_t *slot_ptr, int32_t n_slots, void *k_out,
+                           void *v_out, int64_t n_rows, int32_t *bad, void *hip_stream)
+{
+    if (!k_dense || !v_dense || !keep_ptr || !keep_t || !off || !items || !slot_ptr || !k_out || !v_out) return FAIRKV_EINVAL;
+    if (B < 1 || Hkv < 1 || T < 1 || D < 1 || n_slots < 1 || n_rows < 0) return FAIRKV_EINVAL;
+    if (!aligned16(k_dense) || !aligned16(v_dense) || !aligned16(k_out) || !aligned16(v_out)) return FAIRKV_EINVAL;
+    const int rb = row_bytes_of(D, dtype);
+    if (rb == 0) return FAIRKV_EUNSUPPORTED;
+    PackArgs a{static_cast<const char *>(k_dense), static_cast<const char *>(v_dense), static_cast<char *>(k_out),
+               static_cast<char *>(v_out), keep_ptr, keep_t, off, items, slot_ptr, bad, n_rows, B, Hkv, T};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (rb == 128)
+        hipLaunchKernelGGL(fairkv_pack_kernel<128>, dim3(n_slots), dim3(256), 0, st, a);
+    else if (rb == 256)
+        hipLaunchKernelGGL(fairkv_pack_kernel<256>, dim3(n_slots), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(fairkv_pack_kernel<512>, dim3(n_slots), dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
+}
+
+extern "C" int fairkv_append(const void *k_new, const void *v_new, int32_t B, int32_t Hkv, int32_t D, int32_t dtype,
+                             const int64_t *off, int32_t *len, const int32_t *cap, void *k, void *v, int64_t n_rows,
+                             int32_t *full, void *hip_stream)
+{
+    if (!k_new || !v_new || !off || !len || !cap || !k || !v) return FAIRKV_EINVAL;
+    if (B < 1 || Hkv < 1 || D < 1 || n_rows < 0) return FAIRKV_EINVAL;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k) || !aligned16(v)) return FAIRKV_EINVAL;
+    const int rb = row_bytes_of(D, dtype);
+    if (rb == 0) return FAIRKV_EUNSUPPORTED;
+    const int64_t n_pairs = static_cast<int64_t>(B) * Hkv;
+    if (n_pairs > INT32_MAX) return FAIRKV_EINVAL;
+    AppendArgs a{static_cast<const char *>(k_new), static_cast<const char *>(v_new), static_cast<char *>(k),
+                 static_cast<char *>(v), off, len, cap, full, n_rows, static_cast<int32_t>(n_pairs)};
+    const int64_t threads = n_pairs * (rb / 16);
+    const dim3 grid(static_cast<unsigned>((threads + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (rb == 128)
+        hipLaunchKernelGGL(fairkv_append_kernel<128>, grid, dim3(256), 0, st, a);
+    else if (rb == 256)
+        hipLaunchKernelGGL(fairkv_append_kernel<256>, grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(fairkv_append_kernel<512>, grid, dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
 }

@@ -210,6 +210,30 @@ extern "C" int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, in
     return FAIRKV_OK;
 }
 
+extern "C" int fairkv_plan_grow(fairkv_item *items, int32_t n_items, int32_t B, int32_t Hkv, int32_t *len,
+                                const int32_t *cap)
+{
+    if (!items || !len || !cap || n_items < 0 || B < 1 || Hkv < 1) return FAIRKV_EINVAL;
+    const int64_t n_pairs = static_cast<int64_t>(B) * Hkv;
+    std::vector<char> seen(static_cast<size_t>(n_pairs), 0);
+    for (int32_t i = 0; i < n_items; ++i) {
+        const fairkv_item &it = items[i];
+        if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.n_chunks < 1) return FAIRKV_EINVAL;
+    }
+    for (int32_t i = 0; i < n_items; ++i) {
+        fairkv_item &it = items[i];
+        if (it.chunk != it.n_chunks - 1) continue;
+        const int64_t pair = static_cast<int64_t>(it.b) * Hkv + it.h;
+        if (seen[pair]) return FAIRKV_EINVAL;      // two last chunks for one pair: not a plan
+        seen[pair] = 1;
+        if (len[pair] < cap[pair]) {
+            ++it.tok_count;
+            ++len[pair];
+        }
+    }
+    return FAIRKV_OK;
+}
+
 extern "C" const char *fairkv_strerror(int code)
 {
     switch (code) {
