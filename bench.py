@@ -46,6 +46,9 @@ def parse():
                     help="instead of the benchmark: place the KV heads of one mistral24b-shaped layer on 2, 4 and 8 "
                          "GPUs (static, Best-effort Assignment, Fair-Copying) with fairkv_place and time every GPU's "
                          "share on this GPU (the paper's Section 4.3; busy rate and step time per scheme)")
+    ap.add_argument("--pack", action="store_true",
+                    help="instead of the benchmark: time fairkv_pack (dense cache -> packed ragged cache) on the "
+                         "llama70b budgets")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -248,6 +251,63 @@ def placement_table(seed=0, name="mistral24b"):
             "profile": f"{name} recipe, B={w.B}: summed budgets per KV head = {Wh.tolist()}", "rows": rows}
 
 
+def pack_bench(seed=0, name="llama70b", T=8192, n_slots=None):
+    """The step before the path: fairkv_pack gathers the kept rows of a dense [B][Hkv][T][D] cache into the
+    packed layout.  Bytes per token moved: K and V rows read and written once plus the 4-byte index."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2502_15804_amd as F
+    from paper_2502_15804_amd.runtime import device_compute_units
+
+    w = W.WORKLOADS[name]
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    sets, moved = [], 0
+    n_slots = n_slots or 8 * device_compute_units()
+    for li in range(3):                                   # 3 x 0.5 GB of dense cache: past the memory-side cache
+        lens = W.lens(name, seed=seed, layer=li)
+        keep_ptr, keep_t = W.keep_lists(lens, T, seed=seed + li)
+        off, total = W.packed_offsets(lens)
+        plan = F.fairkv_plan(lens, off, w.B, w.Hkv, F.fairkv_default_params(n_slots, overhead_tokens=16, min_chunk=64))
+        kd = torch.randn((w.B, w.Hkv, T, w.D), device="cuda", dtype=torch.float32).to(tdt)
+        vd = torch.randn((w.B, w.Hkv, T, w.D), device="cuda", dtype=torch.float32).to(tdt)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        sets.append((kd, vd, dev(keep_ptr), dev(keep_t), dev(off.reshape(-1)), dev(plan.items.view(np.uint8).copy()),
+                     dev(plan.slot_ptr), torch.empty((total, w.D), dtype=tdt, device="cuda"),
+                     torch.empty((total, w.D), dtype=tdt, device="cuda")))
+        moved += int(lens.sum()) * (4 * w.D * w.elem_bytes + 4)
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def run_all():
+        for s in sets:
+            F.fairkv_pack(*s, bad)
+
+    run_all()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / reps
+    assert int(bad.item()) == 0
+    gbs = moved / sec / 1e9
+    return {"experiment": "fairkv_pack: gather of the kept rows of a dense cache into the packed ragged layout",
+            "config": {"workload": f"{name} budgets out of a dense cache of T={T} tokens per pair", "n_slots": n_slots,
+                       "layers": len(sets)},
+            "us_per_layer": round(1e6 * sec / len(sets), 2), "value": round(gbs, 1), "unit": "GB/s",
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "kernel": f"fairkv_pack_kernel<{w.D * w.elem_bytes}>", "bytes_per_launch": moved // len(sets)}}
+
+
 def latency_model(seed=0):
     """Section 3.2 of the paper on this GPU: one layer (64 query / 8 KV heads, D=128, bf16), every head with the
     same budget C, batch B; time per decode step through the whole path (plan resident, one launch)."""
@@ -346,6 +406,9 @@ def main():
         return
     if a.placement_table:
         print(json.dumps(placement_table(a.seed)))
+        return
+    if a.pack:
+        print(json.dumps(pack_bench(a.seed, n_slots=a.n_slots)))
         return
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers
