@@ -355,6 +355,40 @@ def latency_model(seed=0):
     return rec
 
 
+def stream_probe(rot, gbs):
+    """The same K/V bytes of the same rotation through fairkv_stream_probe: a reader with the decode kernel's
+    data path and launch shape and nothing to do.  Its rate is the ceiling this path can reach for this size."""
+    import torch
+    import paper_2502_15804_amd as F
+
+    sink = torch.zeros(rot.n_cu, dtype=torch.int32, device="cuda")
+    n = len(rot.layers)
+
+    def run_all():
+        for l in rot.layers:
+            F.fairkv_stream_probe(l.k, l.v, rot.n_cu, sink)
+
+    run_all()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    g.replay()
+    torch.cuda.synchronize()
+    reps = max(3, 640 // n)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / (reps * n)
+    kv_bytes = sum(2 * l.k.numel() * l.k.element_size() for l in rot.layers) / n
+    return {"us_per_layer": round(1e6 * sec, 2), "GBs": round(kv_bytes / sec / 1e9, 1),
+            "decode_rate_over_probe_rate": round(gbs / (kv_bytes / sec / 1e9), 3),
+            "what": "K and V of the same layers streamed HBM -> LDS by 256 workgroups, nothing computed or written"}
+
+
 def cpu_baseline(rot, seconds):
     """The fp64 oracle, as it stands, on the host cores: whole layers of the same workload."""
     import workloads as W
@@ -459,6 +493,7 @@ def main():
             rec[f"gain_vs_{key}"] = round(gbs / (moved2 / ev2 / 1e9), 3)
             del r2
             torch.cuda.empty_cache()
+        rec["stream_probe"] = stream_probe(rot, gbs)
         rec["cpu_baseline"] = cpu_baseline(rot, a.cpu_seconds)
     print(json.dumps(rec))
 

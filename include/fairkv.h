@@ -284,6 +284,14 @@ int fairkv_append(const void *k_new, const void *v_new, int32_t B, int32_t Hkv, 
  * and step; re-plan with fairkv_plan every few hundred steps. */
 int fairkv_plan_grow(fairkv_item *items, int32_t n_items, int32_t B, int32_t Hkv, int32_t *len, const int32_t *cap);
 
+/* Measurement aid, not part of the method: n_workgroups workgroups stream the first bytes_each
+ * bytes (rounded down to a multiple of 4096 * n_workgroups) of the device buffers k and v from HBM
+ * into LDS through the decode kernel's data path and discard them.  The time of this launch is what
+ * a reader without any work achieves for that many bytes; bench.py reports the decode kernel
+ * against it.  sink: any device buffer of n_workgroups words (never written).  No synchronisation. */
+int fairkv_stream_probe(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups, void *sink,
+                        void *hip_stream);
+
 const char *fairkv_strerror(int code);
 int fairkv_version(void);
 

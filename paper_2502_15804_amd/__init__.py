@@ -23,7 +23,7 @@ FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_F
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
-           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_strerror", "fairkv_version")
+           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
 class fairkv_item(ctypes.Structure):
@@ -99,6 +99,8 @@ def lib() -> ctypes.CDLL:
         L.fairkv_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_int64, vp, vp]
         L.fairkv_plan_grow.restype = ctypes.c_int
         L.fairkv_plan_grow.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.fairkv_stream_probe.restype = ctypes.c_int
+        L.fairkv_stream_probe.argtypes = [vp, vp, ctypes.c_int64, i32, vp, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -321,3 +323,19 @@ def fairkv_plan_grow(items: np.ndarray, B: int, Hkv: int, lens: np.ndarray, cap:
     rc = lib().fairkv_plan_grow(items.ctypes.data, items.size, int(B), int(Hkv), lens.ctypes.data, cap.ctypes.data)
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_plan_grow")
+
+
+def fairkv_stream_probe(k, v, n_workgroups, sink, stream=None):
+    """Enqueue the do-nothing reader over all of the device tensors k and v (see the header)."""
+    import torch
+
+    _check_dev(k=k, v=v, sink=sink)
+    if sink.numel() * sink.element_size() < 4 * n_workgroups:
+        raise ValueError("sink too small")
+    if stream is None:
+        stream = torch.cuda.current_stream(k.device)
+    nbytes = min(k.numel() * k.element_size(), v.numel() * v.element_size())
+    rc = lib().fairkv_stream_probe(_ptr(k), _ptr(v), nbytes, int(n_workgroups), _ptr(sink),
+                                   ctypes.c_void_p(stream.cuda_stream))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_stream_probe")

@@ -16,6 +16,7 @@
 #include "decode_mfma.h"
 #include "decode_valu.h"
 #include "pack.h"
+#include "stream_probe.h"
 #include "fairkv.h"
 
 namespace {
@@ -212,5 +213,17 @@ extern "C" int fairkv_append(const void *k_new, const void *v_new, int32_t B, in
         hipLaunchKernelGGL(fairkv_append_kernel<256>, grid, dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL(fairkv_append_kernel<512>, grid, dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
+}
+
+// ---- measurement aid ------------------------------------------------------------------------------
+extern "C" int fairkv_stream_probe(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups,
+                                   void *sink, void *hip_stream)
+{
+    if (!k || !v || !sink || n_workgroups < 1 || bytes_each < 0 || !aligned16(k) || !aligned16(v)) return FAIRKV_EINVAL;
+    ProbeArgs a{static_cast<const char *>(k), static_cast<const char *>(v),
+                bytes_each / n_workgroups / 4096 * 4096, static_cast<uint32_t *>(sink)};
+    if (a.bytes_per_workgroup * kWaves > static_cast<int64_t>(UINT32_MAX)) return FAIRKV_EINVAL;   // 32-bit lane offsets
+    hipLaunchKernelGGL(fairkv_stream_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), a);
     return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
 }
