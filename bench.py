@@ -405,9 +405,63 @@ def cpu_baseline(rot, seconds):
         spent += time.perf_counter() - t0
         done_bytes += rot.bytes[li]
         n_done += 1
+    q, k, v = host[0]                                     # the same oracle on one core, one layer
+    t0 = time.perf_counter()
+    OA.attention(q, k, v, rot.offs[0], rot.lens[0], rot.w.scale, n_threads=1)
+    one = time.perf_counter() - t0
     return {"value": round(done_bytes / spent / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{n_done} whole-layer passes over {len(host)} layer(s) of {rot.w.name}, every output, {spent:.1f} s",
-            "ms_per_layer": round(1e3 * spent / n_done, 2)}
+            "ms_per_layer": round(1e3 * spent / n_done, 2), "ms_per_layer_one_core": round(1e3 * one, 1)}
+
+
+def cold_launch_us(rot):
+    """A launch whose K/V are in no cache: every launch is preceded by a 1 GB fill, both replayed as one HIP
+    graph; the time of the fills alone (a second graph) is subtracted."""
+    import torch
+    junk = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    layers = rot.layers[:8]
+
+    def graph_of(with_launches):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for l in layers:
+                junk.fill_(1)
+                if with_launches:
+                    l.run()
+        return g
+
+    def time_of(g):
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / (5 * len(layers))
+
+    for l in layers:
+        l.run()
+    torch.cuda.synchronize()
+    return round(time_of(graph_of(True)) - time_of(graph_of(False)), 2)
+
+
+def max_split_sweep(a, n_layers, overrides, gbs_fair):
+    """Fair-Copying as the paper states it (equal shares, Algorithm 2's W / copies) with the cap on copies per
+    pair swept: the one-GPU analogue of the paper's sweep over the count of copied heads (Section 5.2.1)."""
+    import torch
+    out = {}
+    for ms in (1, 2, 4, 8, 16, 64):
+        ov = dict(overrides)
+        ov["max_split"] = ms
+        r2 = Rotation(a.workload, n_layers, a.seed, 2, ov)
+        _, ev2, moved2 = timed(r2, max(n_layers * 4, 64), n_layers, not a.no_graph)
+        out[f"max_split={ms}"] = round(moved2 / ev2 / 1e9, 1)
+        del r2
+        torch.cuda.empty_cache()
+    out["fair_line_cut"] = round(gbs_fair, 1)
+    return out
 
 
 def main():
@@ -494,6 +548,8 @@ def main():
             del r2
             torch.cuda.empty_cache()
         rec["stream_probe"] = stream_probe(rot, gbs)
+        rec["cold_single_launch_us"] = cold_launch_us(rot)
+        rec["lpt_equal_split_GBs_by_max_split"] = max_split_sweep(a, n_layers, overrides, gbs)
         rec["cpu_baseline"] = cpu_baseline(rot, a.cpu_seconds)
     print(json.dumps(rec))
 
