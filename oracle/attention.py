@@ -94,6 +94,34 @@ def attention(q, k, v, off, lens, scale, sel=None, n_threads=0):
     return out, lse
 
 
+def attention_multi(q, k, v, off, lens, scale, n_threads=0):
+    """q [B,q_len,Hq,D]: q_len new tokens per sequence whose K/V are already the last q_len rows of
+    every head; new token i sees rows [0, len - (q_len-1-i)).  out [B,q_len,Hq,D], lse [B,q_len,Hq]."""
+    if q.ndim != 4:
+        raise ValueError("q must be [B, q_len, Hq, D]")
+    B, QL, Hq, D = q.shape
+    q3, k, v, dt = _check_inputs(q.reshape(B * QL, Hq, D), k, v)
+    off = np.ascontiguousarray(off, dtype=np.int64)
+    lens = np.ascontiguousarray(lens, dtype=np.int32)
+    Hkv = lens.shape[1]
+    if off.shape != lens.shape or lens.shape[0] != B:
+        raise ValueError("off/lens must be [B,Hkv]")
+    live = lens > 0
+    if live.any() and (int((off + lens)[live].max()) > k.shape[0] or int(off[live].min()) < 0):
+        raise ValueError("a head's rows lie outside K/V")
+    out = np.full((B, QL, Hq, D), np.nan, dtype=np.float64)
+    lse = np.full((B, QL, Hq), np.nan, dtype=np.float64)
+    fn = _load().fairkv_oracle_attn_multi
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                                                               ctypes.c_int]
+    rc = fn(q3.ctypes.data, k.ctypes.data, v.ctypes.data, off.ctypes.data, lens.ctypes.data, B, QL, Hq, Hkv, D, dt,
+            float(scale), out.ctypes.data, lse.ctypes.data, int(n_threads))
+    if rc != 0:
+        raise ValueError("fairkv_oracle_attn_multi rejected its arguments")
+    return out, lse
+
+
 def attention_chunk(q, k, v, b, hq, row0, n, scale):
     """(m, l, acc[D]) of rows [row0, row0+n) of K/V for query q[b, hq]."""
     q, k, v, dt = _check_inputs(q, k, v)

@@ -144,6 +144,62 @@ int fairkv_oracle_attn(const void *q, const void *k, const void *v,
 }
 
 /*
+ * Several new tokens per sequence at once (a draft of q_len tokens being verified): the cache
+ * already holds their K/V as the last q_len rows of every head, and new token i (0-based) sees
+ * the rows before the new tokens that follow it: rows [0, len - (q_len - 1 - i)), none if that
+ * is not positive.  This is ordinary causal attention restricted to the kept tokens; with
+ * q_len = 1 it is fairkv_oracle_attn.  q [B][q_len][Hq][D]; out [B][q_len][Hq][D] and
+ * lse [B][q_len][Hq] are double.  Returns 0, or -1 on bad arguments.
+ */
+int fairkv_oracle_attn_multi(const void *q, const void *k, const void *v,
+                             const int64_t *off, const int32_t *len,
+                             int B, int q_len, int Hq, int Hkv, int D, int dtype, double scale,
+                             double *out, double *lse, int n_threads)
+{
+    if (!q || !k || !v || !off || !len || !out || !lse)
+        return -1;
+    if (B <= 0 || q_len <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0)
+        return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_F32 && dtype != ORACLE_F64)
+        return -1;
+    const int G = Hq / Hkv;
+    const int total = B * q_len * Hq;
+#ifdef _OPENMP
+    if (n_threads > 0)
+        omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int flat = 0; flat < total; ++flat) {
+        const int hq = flat % Hq, i = (flat / Hq) % q_len, b = flat / (Hq * q_len), h = hq / G;
+        const int64_t len_bh = len[b * Hkv + h];
+        const int64_t row0 = off[b * Hkv + h];
+        if (len_bh < 0) {
+            bad = 1;
+            continue;
+        }
+        int64_t n = len_bh - (q_len - 1 - i);
+        if (n < 0)
+            n = 0;
+        double *o = out + (int64_t)flat * D;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        double m, l;
+        scores_and_sums(q, (int64_t)flat * D, k, v, row0, n, D, dtype, scale, s, &m, &l, o);
+        if (n == 0) {
+            lse[flat] = -INFINITY;
+        } else {
+            for (int d = 0; d < D; ++d)
+                o[d] /= l;
+            lse[flat] = m + log(l);
+        }
+        free(s);
+    }
+    return bad ? -1 : 0;
+}
+
+/*
  * One token chunk of one (sequence, query head): rows [off + t0, off + t0 + n)
  * of that head's cache.  Gives the chunk's (m, l, unnormalised acc[D]).  Used
  * only to pin the chunk-merge identity (chunked-and-merged == unchunked).

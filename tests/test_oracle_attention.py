@@ -306,3 +306,28 @@ def test_rejects_rows_past_the_buffer():
     k = np.zeros((3, 2))
     with pytest.raises(ValueError):
         OA.attention(q, k, k, np.array([[2]], np.int64), np.array([[2]], np.int32), 1.0)
+
+
+# ---- several new tokens per sequence --------------------------------------------------------
+def test_multi_token_queries_are_single_token_queries_over_shorter_caches():
+    """New token i of q_len sees everything but the new tokens after it: the same as the single-token
+    oracle (pinned above) run with every length reduced by q_len-1-i."""
+    rng = np.random.default_rng(21)
+    B, Hkv, G, D, QL = 3, 2, 2, 8, 3
+    lens = rng.integers(0, 25, size=(B, Hkv)).astype(np.int32)
+    lens[0, 0], lens[1, 1] = 1, 2                      # shorter than q_len: early tokens see nothing
+    off = np.arange(B * Hkv, dtype=np.int64).reshape(B, Hkv) * 30
+    k = rng.normal(size=(B * Hkv * 30, D))
+    v = rng.normal(size=(B * Hkv * 30, D))
+    q = rng.normal(size=(B, QL, Hkv * G, D))
+    out, lse = OA.attention_multi(q, k, v, off, lens, 0.4)
+    assert out.shape == (B, QL, Hkv * G, D) and lse.shape == (B, QL, Hkv * G)
+    for i in range(QL):
+        ro, rl = OA.attention(np.ascontiguousarray(q[:, i]), k, v, off, np.maximum(lens - (QL - 1 - i), 0), 0.4)
+        assert np.array_equal(out[:, i], ro) and np.array_equal(lse[:, i], rl)
+    assert (out[0, 0, 0:G] == 0).all() and np.isneginf(lse[0, 0, 0:G]).all()     # len 1, first of 3 new tokens
+    o1, l1 = OA.attention_multi(np.ascontiguousarray(q[:, :1]), k, v, off, lens, 0.4)
+    ro, rl = OA.attention(np.ascontiguousarray(q[:, 0]), k, v, off, lens, 0.4)
+    assert np.array_equal(o1[:, 0], ro) and np.array_equal(l1[:, 0], rl)        # q_len = 1 is the plain path
+    with pytest.raises(ValueError):
+        OA.attention_multi(q[:, 0], k, v, off, lens, 0.4)
