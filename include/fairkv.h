@@ -247,6 +247,26 @@ typedef struct {
 int fairkv_place(const int64_t *W, int32_t n_heads, int32_t B, const fairkv_place_params *p,
                  fairkv_share *shares, int32_t shares_cap, int64_t *gpu_load, fairkv_place_summary *summary);
 
+/* Several new tokens per sequence in one call (a draft of q_len tokens being verified, or a short
+ * chunk of prompt): not in the paper; the same path with the G heads of a group and the q_len new
+ * tokens sharing the 16 columns of a matrix-core tile, so K and V are still streamed once.  The
+ * caller has appended the new tokens' K/V first: they are the LAST q_len rows of every pair, and
+ * new token i (0-based) attends rows [0, len - (q_len - 1 - i)) of the pair (causal among the new
+ * tokens; nothing if that is not positive: out 0, lse -inf).  q and out are [B][q_len][Hq][D],
+ * lse [B][q_len][Hq]; everything else as in fairkv_decode_attn, which is the case q_len = 1.
+ * The workspace must hold fairkv_workspace_bytes(n_parts, B*Hkv, G * q_len, D) bytes.
+ * The last chunk of a cut pair must hold at least q_len - 1 tokens (else FAIRKV_EINVAL): the rows
+ * the new tokens hide from one another are masked inside that chunk only.  The FAIR policy makes
+ * no chunk below min_chunk >= 16, so its plans always qualify.
+ * Supported: bf16 inputs, G * q_len in {1, 2, 4, 8, 16} (else FAIRKV_EUNSUPPORTED). */
+int fairkv_decode_attn_multi(const void *q, const void *k, const void *v,
+                             const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                             const int32_t *slot_ptr, int32_t n_slots,
+                             int32_t n_parts, void *workspace, size_t workspace_bytes,
+                             void *out, float *lse,
+                             int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D,
+                             int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream);
+
 /* ---- building and growing the packed cache (the step before the path) ---------------------------
  *
  * fairkv_pack gathers the tokens a per-head compressor kept (Section 2: which entries a method

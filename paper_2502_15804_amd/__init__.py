@@ -23,6 +23,7 @@ FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_F
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
+           "fairkv_decode_attn_multi",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
@@ -101,6 +102,9 @@ def lib() -> ctypes.CDLL:
         L.fairkv_plan_grow.argtypes = [vp, i32, i32, i32, vp, vp]
         L.fairkv_stream_probe.restype = ctypes.c_int
         L.fairkv_stream_probe.argtypes = [vp, vp, ctypes.c_int64, i32, vp, vp]
+        L.fairkv_decode_attn_multi.restype = ctypes.c_int
+        L.fairkv_decode_attn_multi.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
+                                               i32, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -212,7 +216,8 @@ def _ptr(t):
 def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
 
-    Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D]; k, v [rows,D];
+    Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D], or [B,q_len,Hq,D] for
+    several new tokens per sequence (fairkv_decode_attn_multi; out and lse then carry q_len too); k, v [rows,D];
     items: uint8 view of the plan's item array (n_items * 32 bytes); workspace uint8, zero-filled
     before its first use; out [B,Hq,D] float32 or bfloat16; lse float32 [B,Hq] or None.
     items_host and slot_ptr are the plan's HOST arrays (numpy: fairkv_item records, int32
@@ -220,7 +225,10 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
     """
     import torch
 
-    B, Hq, D = q.shape
+    if q.dim() == 4:
+        B, q_len, Hq, D = q.shape
+    else:
+        (B, Hq, D), q_len = q.shape, 1
     dt = {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}
     if q.dtype not in dt or k.dtype != q.dtype or v.dtype != q.dtype or out.dtype not in dt:
         raise TypeError("q/k/v must share bf16 or fp32; out must be bf16 or fp32")
@@ -234,8 +242,10 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
         raise TypeError("slot_ptr must be a contiguous host int32 array")
     if lse is not None and lse.dtype != torch.float32:
         raise TypeError("lse must be float32")
-    if k.shape[1] != D or v.shape != k.shape or tuple(out.shape) != (B, Hq, D) or slot_ptr.size < 2:
+    if k.shape[1] != D or v.shape != k.shape or tuple(out.shape) != tuple(q.shape) or slot_ptr.size < 2:
         raise ValueError("shape mismatch")
+    if lse is not None and tuple(lse.shape) != tuple(q.shape[:-1]):
+        raise ValueError("lse must have q's shape without the last dimension")
     item_bytes = items.numel() * items.element_size()
     if item_bytes % 32 != 0:
         raise ValueError("items must be a whole number of 32-byte records")
@@ -244,14 +254,14 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
         raise TypeError("items_host must be the plan's contiguous item array, as many records as `items`")
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
-    rc = lib().fairkv_decode_attn(
+    rc = lib().fairkv_decode_attn_multi(
         _ptr(q), _ptr(k), _ptr(v), _ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data,
         slot_ptr.size - 1,
         int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _ptr(out), _ptr(lse), B, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
+        _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
         ctypes.c_void_p(stream.cuda_stream))
     if rc != FAIRKV_OK:
-        raise FairKVError(rc, "fairkv_decode_attn")
+        raise FairKVError(rc, "fairkv_decode_attn_multi" if q_len > 1 else "fairkv_decode_attn")
 
 
 def _dtype_code(t):

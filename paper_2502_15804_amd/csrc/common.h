@@ -57,6 +57,10 @@ __device__ __forceinline__ void store_out4(void *out, int out_dtype, size_t idx,
     }
 }
 
+struct DecodeArgs;
+// Where column c of pair (b, h) lives in out (times D) and in lse: [B][q_len][Hq].
+__device__ __forceinline__ size_t out_row(const DecodeArgs &a, int b, int h, int c);
+
 // Partial results travel between workgroups that may sit on different XCDs, whose L2 caches
 // are not coherent with each other.  Agent-scope relaxed atomics are plain 4-byte stores and
 // loads that go through to the level all XCDs share, without the cache-wide write-back and
@@ -88,6 +92,9 @@ struct DecodeArgs {
     void *out;
     float *lse;
     int32_t B, Hq, Hkv, out_dtype, n_parts;
+    int32_t q_len, g_shift;     // new tokens per sequence; log2 of the query heads per KV head.  A kernel's
+                                // template parameter G counts columns: q_len * (1 << g_shift), column
+                                // c = new token (c >> g_shift), head (c & mask) of the group
     float scale_log2;           // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
     // What a workgroup needs before it has read anything from memory, riding in the kernel arguments:
     int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1])
@@ -97,6 +104,12 @@ struct DecodeArgs {
 };
 constexpr int kEarlyTok = 192;            // tokens of a slot's first item that the early start may request
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+__device__ __forceinline__ size_t out_row(const DecodeArgs &a, int b, int h, int c)
+{
+    const int tok = c >> a.g_shift, g = c & ((1 << a.g_shift) - 1);
+    return (static_cast<size_t>(b) * a.q_len + tok) * a.Hq + (h << a.g_shift) + g;
+}
 
 // Layout facts shared by the stages.  A row of K or V is LPR 16-byte pieces; one wave-wide
 // 16-byte-per-lane access covers RPI whole rows, so every global access is a run of
@@ -126,10 +139,11 @@ __device__ __forceinline__ float2 fetch_f32x2(const float *p)
 // wait in LDS until the slot's list is done (or the buffer is full) and are then published
 // together, so that the hand-over, which costs several memory round trips, happens once per
 // workgroup and not in the middle of the stream.
-constexpr int kPend = 3;
+constexpr int pend_slots(int D, int G) { return D * G > 1024 ? 2 : 3; }   // LDS is the limit
 
 template <int D, int G>
 struct PendingParts {
+    static constexpr int kPend = pend_slots(D, G);
     __attribute__((aligned(16))) float o[kPend][G * D];
     float ml[kPend][G * 2];
     int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend], last[kPend];
@@ -169,6 +183,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
     // four consecutive coordinates of one query head.  The loads of ALL pairs to merge are issued
     // before any is used, so the hand-over costs one memory round trip, not one per pair.
     constexpr int D4 = D / 4;
+    constexpr int kPend = pend_slots(D, G);
     for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
         const int g = idx / D4, d = (idx % D4) * 4;
         float2 ml[kPend][kMergeBatch], o01[kPend][kMergeBatch], o23[kPend][kMergeBatch];
@@ -222,11 +237,11 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
                 m_star = m_new;
             }
             const int b = pair / a.Hkv, h = pair % a.Hkv;
-            const size_t oi = (static_cast<size_t>(b) * a.Hq + h * G + g) * D + d;
+            const size_t orow = out_row(a, b, h, g);
             const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
-            store_out4(a.out, a.out_dtype, oi, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
+            store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             if (d == 0 && a.lse)
-                a.lse[b * a.Hq + h * G + g] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
+                a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         }
     }
     if (threadIdx.x < n_pend && pend.last[threadIdx.x])   // ready for the next call on this workspace
@@ -275,12 +290,11 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
             l_star += ml[w].y * f;
         }
         if (whole_pair) {
-            const size_t oi = (static_cast<size_t>(b) * a.Hq + h * G + g) * D + d;
+            const size_t orow = out_row(a, b, h, g);
             const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
-            store_out4(a.out, a.out_dtype, oi, make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
+            store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
             if (d == 0 && a.lse)
-                a.lse[b * a.Hq + h * G + g] =
-                    l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
+                a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         } else {
             *reinterpret_cast<float4 *>(&pend.o[n_pend][idx * 4]) = acc;
             if (d == 0) {
@@ -297,7 +311,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
             pend.n_chunks[n_pend] = it.n_chunks;
         }
         ++n_pend;
-        if (n_pend == kPend) {
+        if (n_pend == pend_slots(D, G)) {
             flush_pending<D, G>(a, pend, n_pend);
             return;
         }

@@ -206,10 +206,18 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     };
 
     // Fetch of the G query rows of pair (b, h) into one of the wave's q buffers: exactly QL loads.
+    // Column c = (new token c >> g_shift, head c & mask) of q [B][q_len][Hq][D]: the heads of one new
+    // token are contiguous, the new tokens are Hq rows apart.
     auto fetch_q = [&](int b, int h, int buf) {
-        const char *src = static_cast<const char *>(a.q) + (static_cast<size_t>(b) * a.Hq + h * G) * ROWB;
+        const char *src = static_cast<const char *>(a.q) +
+                          (static_cast<size_t>(b) * a.q_len * a.Hq + (h << a.g_shift)) * ROWB;
 #pragma unroll
-        for (int i = 0; i < QL; ++i) load16_to_lds(src, min(i * 1024 + lane * 16, QBYTES - 16), q_lds + buf * QBUF + i * 1024);
+        for (int i = 0; i < QL; ++i) {
+            const int o = min(i * 1024 + lane * 16, QBYTES - 16);      // byte o of the [G][ROWB] image in LDS
+            const int c = o / ROWB;
+            const int row = (c >> a.g_shift) * a.Hq + (c & ((1 << a.g_shift) - 1));
+            load16_to_lds(src, row * ROWB + o % ROWB, q_lds + buf * QBUF + i * 1024);
+        }
     };
 
     // Fetch of this wave's 32 of the kTable items that start at `first`: one load.  Past the end of
@@ -316,6 +324,11 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             it.part = __builtin_amdgcn_readfirstlane(table[ci].part);
             const int n = __builtin_amdgcn_readfirstlane(table[ci].n);
             const int my_tiles = tiles_of(n);
+            // Several new tokens per sequence: their K/V rows are the last q_len rows of the pair, and
+            // new token j does not see the rows of the new tokens after it.  Only the pair's last
+            // chunk holds such rows; n_col = tokens of this item the lane's column may see.
+            const int hidden_max = it.chunk == it.n_chunks - 1 ? a.q_len - 1 : 0;
+            const int n_col = n - (it.chunk == it.n_chunks - 1 ? a.q_len - 1 - (min(l16, G - 1) >> a.g_shift) : 0);
             bf16x8_t qb[NSL];
 #pragma unroll
             for (int s = 0; s < NSL; ++s) qb[s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
@@ -356,14 +369,15 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
 #pragma unroll
                 for (int s = 0; s < NSL; ++s)
                     sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw[s]), qb[s], sacc, 0, 0, 0);
-                const int nv = n - (wave + t * kWaves) * kTok;     // valid tokens of the tile if below kTok
+                const int tok0 = (wave + t * kWaves) * kTok;
+                const bool masked = n - hidden_max - tok0 < kTok;    // some column does not see the whole tile
                 float sv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * a.scale_log2;
-                if (nv < kTok) {
+                if (masked) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (4 * lq + i >= nv) sv[i] = -INFINITY;
+                        if (4 * lq + i >= n_col - tok0) sv[i] = -INFINITY;
                 }
 
                 // ---- raise the reference maximum if some score is far above it (always on the first tile)
@@ -386,6 +400,11 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 float p[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_run);
+                if (masked) {     // a column that has seen nothing yet has m = -inf: its weights are 0, not exp2(nan)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (sv[i] == -INFINITY) p[i] = 0.f;
+                }
                 const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) l_run += static_cast<float>(pb[i]);

@@ -46,6 +46,7 @@ hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
     case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4>), grid, block, 0, st, a); break;
     case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -91,8 +92,18 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
                                   int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
                                   void *hip_stream)
 {
+    return fairkv_decode_attn_multi(q, k, v, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                                    workspace_bytes, out, lse, B, 1, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream);
+}
+
+extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, const fairkv_item *items,
+                                        const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
+                                        int32_t n_slots, int32_t n_parts, void *workspace, size_t workspace_bytes,
+                                        void *out, float *lse, int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv,
+                                        int32_t D, int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream)
+{
     if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
-    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0) return FAIRKV_EINVAL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1) return FAIRKV_EINVAL;
     if (Hq % Hkv != 0) return FAIRKV_EINVAL;
     if (n_parts < n_items) return FAIRKV_EINVAL;
     if (n_slots > FAIRKV_MAX_SLOTS) return FAIRKV_EUNSUPPORTED;
@@ -104,6 +115,9 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
         if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
         if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
         if (it.part < it.chunk || it.part - it.chunk + it.n_chunks > n_parts) return FAIRKV_EINVAL;
+        // the rows new tokens hide from one another (the last q_len - 1 of a pair) must not reach
+        // back beyond the pair's last chunk: the kernel masks inside that chunk only
+        if (q_len > 1 && it.n_chunks > 1 && it.chunk == it.n_chunks - 1 && it.tok_count < q_len - 1) return FAIRKV_EINVAL;
     }
     if (!(scale == scale) || std::isinf(scale)) return FAIRKV_EINVAL;
     if (in_dtype != FAIRKV_BF16 && in_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
@@ -111,9 +125,13 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     const int G = Hq / Hkv;
     if (D != 64 && D != 128) return FAIRKV_EUNSUPPORTED;
     if (G != 1 && G != 2 && G != 4 && G != 8) return FAIRKV_EUNSUPPORTED;
+    // columns of a pair: G heads times q_len new tokens; they share the 16 columns of one MFMA tile
+    const int64_t cols = static_cast<int64_t>(G) * q_len;
+    if (cols != 1 && cols != 2 && cols != 4 && cols != 8 && cols != 16) return FAIRKV_EUNSUPPORTED;
+    if (q_len > 1 && (in_dtype != FAIRKV_BF16 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
     if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items) || !aligned16(out)) return FAIRKV_EINVAL;
-    if (static_cast<int64_t>(B) * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
-    const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, G, D);
+    if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
+    const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
     if (!workspace || workspace_bytes < need) return FAIRKV_EWORKSPACE;
     if (!aligned16(workspace)) return FAIRKV_EINVAL;
 
@@ -138,7 +156,7 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     a.arrivals = reinterpret_cast<int32_t *>(ws);
     ws += align256(static_cast<size_t>(B) * Hkv * sizeof(int32_t));
     a.part_ml = reinterpret_cast<float *>(ws);
-    ws += align256(static_cast<size_t>(n_parts) * G * 2 * sizeof(float));
+    ws += align256(static_cast<size_t>(n_parts) * cols * 2 * sizeof(float));
     a.part_o = reinterpret_cast<float *>(ws);
     a.out = out;
     a.lse = lse;
@@ -147,11 +165,14 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
     a.Hkv = Hkv;
     a.out_dtype = out_dtype;
     a.n_parts = n_parts;
+    a.q_len = q_len;
+    a.g_shift = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : 3;
     a.scale_log2 = scale * kLog2e;
 
     hipError_t e;
     if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())
-        e = D == 128 ? launch_mfma<128>(G, a, n_slots, st) : launch_mfma<64>(G, a, n_slots, st);
+        e = D == 128 ? launch_mfma<128>(static_cast<int>(cols), a, n_slots, st)
+                     : launch_mfma<64>(static_cast<int>(cols), a, n_slots, st);
     else if (in_dtype == FAIRKV_BF16)
         e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_slots, st);
     else

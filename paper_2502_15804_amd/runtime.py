@@ -27,7 +27,8 @@ class DecodeLayer:
 
         dev = q.device
         self.q, self.k, self.v = q, k, v
-        self.B, self.Hq, self.D = q.shape
+        self.q_len = q.shape[1] if q.dim() == 4 else 1     # several new tokens per sequence: q [B,q_len,Hq,D]
+        self.B, self.Hq, self.D = q.shape[0], q.shape[-2], q.shape[-1]
         lens_h = np.ascontiguousarray(np.asarray(lens, dtype=np.int32))
         off_h = np.ascontiguousarray(np.asarray(off, dtype=np.int64))
         self.Hkv = lens_h.shape[1]
@@ -37,14 +38,14 @@ class DecodeLayer:
             params = fairkv_default_params(device_compute_units(dev))
         self.plan: Plan = fairkv_plan(lens_h, off_h, self.B, self.Hkv, params)
         self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
-        need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G, self.D)
+        need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G * self.q_len, self.D)
         if workspace is None:
             workspace = torch.zeros(need, dtype=torch.uint8, device=dev)   # arrival counters start at zero
         elif workspace.numel() < need:
             raise ValueError("shared workspace too small for this layer")
         self.workspace = workspace
-        self.out = torch.empty((self.B, self.Hq, self.D), dtype=out_dtype or torch.float32, device=dev)
-        self.lse = torch.empty((self.B, self.Hq), dtype=torch.float32, device=dev) if want_lse else None
+        self.out = torch.empty(tuple(q.shape), dtype=out_dtype or torch.float32, device=dev)
+        self.lse = torch.empty(tuple(q.shape[:-1]), dtype=torch.float32, device=dev) if want_lse else None
 
     def run(self, stream=None):
         fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.items, self.plan.slot_ptr, self.plan.n_parts,

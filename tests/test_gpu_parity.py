@@ -275,3 +275,65 @@ def test_layers_sharing_one_workspace_on_one_stream():
     for l, (lens, off, q, k, v) in zip(layers, cases):
         ro, _ = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, small.scale)
         assert np.abs(l.out.cpu().numpy().astype(np.float64) - ro).max() <= small.tol
+
+
+# ---- several new tokens per sequence (fairkv_decode_attn_multi) ---------------------------------
+@pytest.mark.parametrize("D,G,QL", [(128, 8, 2), (128, 4, 4), (128, 4, 2), (128, 2, 2), (128, 1, 4), (128, 2, 8),
+                                    (128, 1, 16), (64, 8, 2), (64, 2, 4), (64, 1, 2)])
+def test_several_new_tokens_per_sequence(D, G, QL):
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    rng = np.random.default_rng(1000 * D + 10 * G + QL)
+    B, Hkv = 3, 2
+    lens = rng.integers(QL, 700, size=(B, Hkv)).astype(np.int32)
+    lens[0, 0] = max(QL - 1, 1)      # shorter than the draft: the first new tokens see nothing or little
+    lens[1, 1] = 0                   # an empty head
+    lens[2, 0] = 64 * 5              # the last tile of the last chunk is full
+    lens[2, 1] = 64 * 3 + 1
+    w = W.Workload("case", B, Hkv * G, Hkv, D, "bf16", 1, 1e-2, "")
+    off, total = W.packed_offsets(lens, gap_rows=2)
+    g = torch.Generator().manual_seed(G * 100 + QL)
+    q = torch.randn((B, QL, Hkv * G, D), generator=g).to(torch.bfloat16)
+    _, k, v = W.make_qkv(w, total + 8, seed=QL)
+    ro, rl = OA.attention_multi(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+    for policy, n_slots, mc in ((3, 16, 32), (0, 16, 32), (3, 5, 16), (3, 300, 16), (2, 40, 64)):
+        p = F.fairkv_default_params(256, policy=policy, n_slots=n_slots, min_chunk=mc, oversub=2)
+        layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p)
+        it = layer.plan.items
+        short_tail = ((it["n_chunks"] > 1) & (it["chunk"] == it["n_chunks"] - 1) & (it["tok_count"] < QL - 1)).any()
+        if short_tail:               # equal shares can leave a last chunk shorter than the rows to hide: refused
+            assert policy == 2
+            with pytest.raises(F.FairKVError) as e:
+                layer.run()
+            assert e.value.code == F.FAIRKV_EINVAL
+            continue
+        for _ in range(2):           # the second call finds the counters the first one left
+            layer.out.fill_(float("nan"))
+            layer.lse.fill_(float("nan"))
+            layer.run()
+            torch.cuda.synchronize()
+        out = layer.out.cpu().numpy().astype(np.float64)
+        lse = layer.lse.cpu().numpy().astype(np.float64)
+        assert out.shape == ro.shape and np.isfinite(out).all()
+        assert np.abs(out - ro).max() <= w.tol, (policy, n_slots, np.abs(out - ro).max())
+        empty = np.isneginf(rl)
+        assert (np.isneginf(lse) == empty).all() and (out[empty] == 0).all()
+        assert np.abs(lse[~empty] - rl[~empty]).max() <= w.tol
+
+
+def test_several_new_tokens_argument_checks():
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    lens = np.full((1, 1), 40, np.int32)
+    off, total = W.packed_offsets(lens)
+    w = W.Workload("case", 1, 8, 1, 128, "bf16", 1, 1e-2, "")
+    _, k, v = W.make_qkv(w, total, seed=0)
+    q = torch.randn((1, 3, 8, 128)).to(torch.bfloat16)            # 8 heads x 3 tokens = 24 columns: not a supported count
+    with pytest.raises(F.FairKVError) as e:
+        DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale).run()
+    assert e.value.code == F.FAIRKV_EUNSUPPORTED
+    w32 = W.Workload("case", 1, 2, 1, 64, "f32", 1, 1e-5, "")
+    _, k32, v32 = W.make_qkv(w32, total, seed=0)
+    with pytest.raises(F.FairKVError) as e:                       # fp32 inputs take the single-token path only
+        DecodeLayer(torch.randn((1, 2, 2, 64)).cuda(), k32.cuda(), v32.cuda(), off, lens, w32.scale).run()
+    assert e.value.code == F.FAIRKV_EUNSUPPORTED
