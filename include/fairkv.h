@@ -159,7 +159,8 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * combines them (log-sum-exp merge), so no second launch is needed.
  *
  * q          device [B][Hq][D], element type in_dtype, 16-byte aligned
- * k, v       device [n_rows][D], element type in_dtype, 16-byte aligned
+ * k, v       device [n_rows][D], element type in_dtype, 16-byte aligned; every item must lie inside:
+ *            row + tok_count <= n_rows (else FAIRKV_EINVAL)
  * items      device [n_items]: the items of a plan made by fairkv_plan from this cache's len
  *            and off, copied to the device by the caller.  The kernels read exactly the rows
  *            the items name.
@@ -182,7 +183,7 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * n_slots <= FAIRKV_MAX_SLOTS (else FAIRKV_EUNSUPPORTED).
  * Calls that share a workspace must have the same B * Hkv and be ordered on one stream.
  */
-int fairkv_decode_attn(const void *q, const void *k, const void *v,
+int fairkv_decode_attn(const void *q, const void *k, const void *v, int64_t n_rows,
                        const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
                        const int32_t *slot_ptr, int32_t n_slots,
                        int32_t n_parts, void *workspace, size_t workspace_bytes,
@@ -259,7 +260,7 @@ int fairkv_place(const int64_t *W, int32_t n_heads, int32_t B, const fairkv_plac
  * the new tokens hide from one another are masked inside that chunk only.  The FAIR policy makes
  * no chunk below min_chunk >= 16, so its plans always qualify.
  * Supported: bf16 inputs, G * q_len in {1, 2, 4, 8, 16} (else FAIRKV_EUNSUPPORTED). */
-int fairkv_decode_attn_multi(const void *q, const void *k, const void *v,
+int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_t n_rows,
                              const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
                              const int32_t *slot_ptr, int32_t n_slots,
                              int32_t n_parts, void *workspace, size_t workspace_bytes,

@@ -89,8 +89,8 @@ def lib() -> ctypes.CDLL:
         L.fairkv_workspace_bytes.restype = ctypes.c_size_t
         L.fairkv_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.fairkv_decode_attn.restype = ctypes.c_int
-        L.fairkv_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
-                                         i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.fairkv_decode_attn.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp,
+                                         vp, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_place.restype = ctypes.c_int
         L.fairkv_place.argtypes = [vp, i32, i32, ctypes.POINTER(fairkv_place_params), vp, i32, vp,
                                    ctypes.POINTER(fairkv_place_summary)]
@@ -103,8 +103,9 @@ def lib() -> ctypes.CDLL:
         L.fairkv_stream_probe.restype = ctypes.c_int
         L.fairkv_stream_probe.argtypes = [vp, vp, ctypes.c_int64, i32, vp, vp]
         L.fairkv_decode_attn_multi.restype = ctypes.c_int
-        L.fairkv_decode_attn_multi.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t, vp, vp,
-                                               i32, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.fairkv_decode_attn_multi.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp,
+                                               ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                               ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -255,7 +256,7 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     rc = lib().fairkv_decode_attn_multi(
-        _ptr(q), _ptr(k), _ptr(v), _ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data,
+        _ptr(q), _ptr(k), _ptr(v), k.shape[0], _ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data,
         slot_ptr.size - 1,
         int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),

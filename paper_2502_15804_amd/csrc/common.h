@@ -92,6 +92,7 @@ struct DecodeArgs {
     void *out;
     float *lse;
     int32_t B, Hq, Hkv, out_dtype, n_parts;
+    int64_t n_rows;             // rows of k and of v
     int32_t q_len, g_shift;     // new tokens per sequence; log2 of the query heads per KV head.  A kernel's
                                 // template parameter G counts columns: q_len * (1 << g_shift), column
                                 // c = new token (c >> g_shift), head (c & mask) of the group

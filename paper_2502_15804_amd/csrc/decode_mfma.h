@@ -275,7 +275,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
         if (threadIdx.x < nb) {
             const fairkv_item it = raw[threadIdx.x];
             const bool ok = it.b >= 0 && it.b < a.B && it.h >= 0 && it.h < a.Hkv && it.row >= 0 && it.part >= 0 &&
-                            it.part < a.n_parts && it.n_chunks >= 1 && it.chunk >= 0 && it.chunk <= it.part;
+                            it.part < a.n_parts && it.n_chunks >= 1 && it.chunk >= 0 && it.chunk <= it.part &&
+                            it.row + max(it.tok_count, 0) <= a.n_rows;
             int n = ok ? max(it.tok_count, 0) : 0;      // a foreign item reads nothing
             if (early && threadIdx.x == 0)              // its first tiles are on their way, as many as n0 said
                 n = n0 < kEarlyTok ? n0 : max(n, kEarlyTok);

@@ -34,7 +34,9 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
     const fairkv_item it = a.items[ii];
     const int b = it.b, h = it.h;
     // an item that does not belong to this problem is skipped by the whole workgroup
-    if (b < 0 || b >= a.B || h < 0 || h >= a.Hkv || it.row < 0 || it.part < 0 || it.part >= a.n_parts) continue;
+    if (b < 0 || b >= a.B || h < 0 || h >= a.Hkv || it.row < 0 || it.part < 0 || it.part >= a.n_parts ||
+        it.row + max(it.tok_count, 0) > a.n_rows)
+        continue;
     const int n = max(it.tok_count, 0);
     const int n_tiles = (n + kTile - 1) / kTile;
 

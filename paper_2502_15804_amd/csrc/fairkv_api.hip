@@ -84,7 +84,7 @@ extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32
            align256(static_cast<size_t>(n_pairs) * sizeof(int32_t));
 }
 
-extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, const fairkv_item *items,
+extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
                                   const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
                                   int32_t n_slots,
                                   int32_t n_parts, void *workspace,
@@ -92,18 +92,19 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, c
                                   int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
                                   void *hip_stream)
 {
-    return fairkv_decode_attn_multi(q, k, v, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+    return fairkv_decode_attn_multi(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
                                     workspace_bytes, out, lse, B, 1, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream);
 }
 
-extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, const fairkv_item *items,
+extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_t n_rows,
+                                        const fairkv_item *items,
                                         const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
                                         int32_t n_slots, int32_t n_parts, void *workspace, size_t workspace_bytes,
                                         void *out, float *lse, int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv,
                                         int32_t D, int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream)
 {
     if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
-    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1) return FAIRKV_EINVAL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1 || n_rows < 0) return FAIRKV_EINVAL;
     if (Hq % Hkv != 0) return FAIRKV_EINVAL;
     if (n_parts < n_items) return FAIRKV_EINVAL;
     if (n_slots > FAIRKV_MAX_SLOTS) return FAIRKV_EUNSUPPORTED;
@@ -113,6 +114,7 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
     for (int32_t i = 0; i < n_items; ++i) {
         const fairkv_item &it = items_host[i];
         if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
+        if (it.row + it.tok_count > n_rows) return FAIRKV_EINVAL;      // the kernel reads exactly these rows of K and V
         if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
         if (it.part < it.chunk || it.part - it.chunk + it.n_chunks > n_parts) return FAIRKV_EINVAL;
         // the rows new tokens hide from one another (the last q_len - 1 of a pair) must not reach
@@ -165,6 +167,7 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
     a.Hkv = Hkv;
     a.out_dtype = out_dtype;
     a.n_parts = n_parts;
+    a.n_rows = n_rows;
     a.q_len = q_len;
     a.g_shift = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : 3;
     a.scale_log2 = scale * kLog2e;

@@ -168,10 +168,10 @@ def test_decode_attn_validates_before_any_launch():
         return it
 
     def call(q=fake, k=fake, v=fake, items=fake, ih=good_item, n_items=1, sp=good_sp, n_slots=1, n_parts=1, ws=fake,
-             ws_bytes=1 << 30, out=fake, lse=None, B=1, Hq=8, Hkv=1, D=128, idt=0, odt=1, scale=0.1):
+             ws_bytes=1 << 30, out=fake, lse=None, B=1, Hq=8, Hkv=1, D=128, idt=0, odt=1, scale=0.1, n_rows=5):
         spp = sp.ctypes.data if sp is not None else None
         ihp = ih.ctypes.data if ih is not None else None
-        return L.fairkv_decode_attn(q, k, v, items, ihp, n_items, spp, n_slots, n_parts, ws, ws_bytes, out, lse,
+        return L.fairkv_decode_attn(q, k, v, n_rows, items, ihp, n_items, spp, n_slots, n_parts, ws, ws_bytes, out, lse,
                                     B, Hq, Hkv, D, idt, odt, scale, None)
 
     assert call(ih=None) == F.FAIRKV_EINVAL
@@ -179,6 +179,8 @@ def test_decode_attn_validates_before_any_launch():
                 item(part=1), item(n_chunks=2, chunk=1, part=0), item(n_chunks=2)):
         assert call(ih=bad) == F.FAIRKV_EINVAL, bad
 
+    assert call(n_rows=4) == F.FAIRKV_EINVAL                       # the item's rows run past the end of K and V
+    assert call(ih=item(row=1)) == F.FAIRKV_EINVAL
     assert call(q=None) == F.FAIRKV_EINVAL
     assert call(out=None) == F.FAIRKV_EINVAL
     assert call(items=None) == F.FAIRKV_EINVAL
