@@ -138,12 +138,13 @@ int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, int32_t Hkv, 
                 fairkv_plan_summary *summary);
 
 /* Bytes of device workspace fairkv_decode_attn needs: fp32 partial outputs and softmax
- * statistics for n_parts items, plus one arrival counter per pair.  0 on bad arguments.
- * Layout: the counters first (n_pairs int32, rounded up to 256 bytes), then statistics and
- * partial outputs.  The first 256-byte-rounded 4 * n_pairs bytes must be zero before the
- * first use (the arrival counters start at zero); every completed call leaves them zero
- * again, whatever its plan, so calls with the same B * Hkv that are ordered on one stream
- * may share one workspace. */
+ * statistics for n_parts items, plus the arrival counters of the hand-over.  0 on bad arguments.
+ * Layout: the counters first (fairkv_workspace_counter_bytes(n_pairs) bytes: one per pair and
+ * one per group of 8 pieces of a pair cut 32 ways or more; their number depends on n_pairs alone),
+ * then statistics and partial outputs.  The counter bytes must be zero before the first use;
+ * every completed call leaves them zero again, whatever its plan, so calls with the same
+ * B * Hkv that are ordered on one stream may share one workspace. */
+size_t fairkv_workspace_counter_bytes(int32_t n_pairs);
 size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D);
 
 /*

@@ -22,7 +22,8 @@ FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_F
 
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
-EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_decode_attn",
+EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_workspace_counter_bytes",
+           "fairkv_decode_attn",
            "fairkv_decode_attn_multi",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
@@ -86,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.fairkv_plan.restype = ctypes.c_int
         L.fairkv_plan.argtypes = [vp, i64p, i32, i32, ctypes.POINTER(fairkv_plan_params), vp, i32, vp, vp,
                                   ctypes.POINTER(fairkv_plan_summary)]
+        L.fairkv_workspace_counter_bytes.restype = ctypes.c_size_t
+        L.fairkv_workspace_counter_bytes.argtypes = [i32]
         L.fairkv_workspace_bytes.restype = ctypes.c_size_t
         L.fairkv_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.fairkv_decode_attn.restype = ctypes.c_int
@@ -204,6 +207,10 @@ def fairkv_place(W, B: int, tp: int, max_extra: int = 0, max_copies: int = 1, mo
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_place")
     return Placement(shares[:s.n_shares].copy(), load, s, p)
+
+
+def fairkv_workspace_counter_bytes(n_pairs: int) -> int:
+    return int(lib().fairkv_workspace_counter_bytes(int(n_pairs)))
 
 
 def fairkv_workspace_bytes(n_parts: int, n_pairs: int, G: int, D: int) -> int:

@@ -88,10 +88,11 @@ struct DecodeArgs {
     const fairkv_item *items;   // grouped by slot
     float *part_o;              // [n_parts][G][D]   unnormalised outputs relative to the item's maximum
     float *part_ml;             // [n_parts][G][2]   (maximum in log2 units, sum of weights)
-    int32_t *arrivals;          // [B*Hkv] items of a cut pair that have delivered their partial; 0 between calls
+    int32_t *arrivals;          // [B*Hkv] items (or groups of items) of a cut pair that have delivered; 0 between calls
+    int32_t *group_arrivals;    // [n_group_counters] the same per group of kGroup items, index first part + group
     void *out;
     float *lse;
-    int32_t B, Hq, Hkv, out_dtype, n_parts;
+    int32_t B, Hq, Hkv, out_dtype, n_parts, n_group_counters;
     int64_t n_rows;             // rows of k and of v
     int32_t q_len, g_shift;     // new tokens per sequence; log2 of the query heads per KV head.  A kernel's
                                 // template parameter G counts columns: q_len * (1 << g_shift), column
@@ -147,7 +148,8 @@ struct PendingParts {
     static constexpr int kPend = pend_slots(D, G);
     __attribute__((aligned(16))) float o[kPend][G * D];
     float ml[kPend][G * 2];
-    int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend], last[kPend];
+    int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend];
+    int32_t role[kPend], src_first[kPend], src_stride[kPend], src_count[kPend];   // what this workgroup merges, if anything
 };
 
 // s_waitcnt vmcnt(0), once as an instruction the compiler accounts for (simm16 of gfx9: vmcnt 0,
@@ -158,31 +160,33 @@ __device__ __forceinline__ void drain_vmem()
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// Hand over the pending partials: publish them, wait until the stores are acknowledged,
-// count the workgroup in for each pair, and merge every pair for which it turned out to be
-// the last one (the log-sum-exp merge; that pair's counter goes back to zero).  Called by all threads.
-template <int D, int G>
-__device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<D, G> &pend, int &n_pend)
+// Hand over the pending partials.  Called by all threads of the workgroup.
+//
+// A pair cut into fewer than kDeepFrom pieces: publish the partial, wait until the stores are
+// acknowledged, count in on the pair's counter; the workgroup that finds itself last merges the
+// pair's partials (all of them were published before their workgroups counted in):
+//   m* = max_c m_c,  l* = sum_c l_c 2^(m_c - m*),  out = sum_c o_c 2^(m_c - m*) / l*
+// (exact in real arithmetic, so a cut pair gives what the whole pair would) and sets the counter
+// back to zero.
+//
+// A pair cut into more pieces would make one workgroup fetch all of them at the rate of a single
+// compute unit (79 pieces of a 16k-token head: 14 us).  Its pieces form groups of kGroup
+// consecutive ones, each group with a counter of its own: the last piece of a group to arrive
+// merges the group into one partial (m*, l*, sum_c o_c 2^(m_c - m*), not divided), stores it in the
+// slot of the group's first piece, waits for the acknowledgement and only then counts in on the
+// pair's counter, on which the last GROUP to arrive merges the group partials.  Two short merges
+// by different workgroups instead of one long one.
+constexpr int kGroup = 8;
+// One merge by one workgroup costs about 0.7 us per kMergeBatch partials; the two-level way costs about
+// 4 us of fixed round trips plus the short final merge.  It pays from about 30 pieces on.
+constexpr int kDeepFrom = 32;
+enum { kRoleNone = 0, kRoleFinal = 1, kRoleGroup = 2 };
+
+template <int D, int G, bool DEEP>
+__device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
 {
-    __syncthreads();
-    for (int p = 0; p < n_pend; ++p) {
-        const size_t base = static_cast<size_t>(pend.part[p]) * G;
-        for (int idx = threadIdx.x; idx < G * D / 4; idx += kThreads)
-            publish_f32x4(a.part_o + base * D + idx * 4, *reinterpret_cast<const float4 *>(&pend.o[p][idx * 4]));
-        if (threadIdx.x < G * 2) publish_f32(a.part_ml + base * 2 + threadIdx.x, pend.ml[p][threadIdx.x]);
-    }
-    drain_vmem();                                      // this thread's stores have reached the shared level ...
-    __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
-    if (threadIdx.x < n_pend)
-        pend.last[threadIdx.x] = __hip_atomic_fetch_add(a.arrivals + pend.pair[threadIdx.x], 1, __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT) == pend.n_chunks[threadIdx.x] - 1;
-    __syncthreads();
-    // Merge every pair for which this workgroup was the last to count in (all of that pair's
-    // partials were published before their workgroups counted in):
-    //   m* = max_c m_c,  l* = sum_c l_c 2^(m_c - m*),  out = sum_c o_c 2^(m_c - m*) / l*
-    // (exact in real arithmetic, so a cut pair gives what the whole pair would).  A thread owns
-    // four consecutive coordinates of one query head.  The loads of ALL pairs to merge are issued
-    // before any is used, so the hand-over costs one memory round trip, not one per pair.
+    // A thread owns four consecutive coordinates of one column.  The first batch of loads of ALL
+    // pending merges is issued before any is used: one memory round trip, not one per pair.
     constexpr int D4 = D / 4;
     constexpr int kPend = pend_slots(D, G);
     for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
@@ -190,12 +194,11 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
         float2 ml[kPend][kMergeBatch], o01[kPend][kMergeBatch], o23[kPend][kMergeBatch];
 #pragma unroll
         for (int p = 0; p < kPend; ++p) {
-            if (p >= n_pend || !pend.last[p]) continue;
-            const int nc = pend.n_chunks[p], p0 = pend.first_part[p];
-            if (p0 < 0 || p0 + nc > a.n_parts) continue;
+            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
+            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
-                const size_t pg = static_cast<size_t>(p0 + min(j, nc - 1)) * G + g;   // past the end: weight 0 below
+                const size_t pg = static_cast<size_t>(p0 + st * min(j, nc - 1)) * G + g;   // past the end: weight 0 below
                 ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
                 o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
                 o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
@@ -203,15 +206,14 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
         }
 #pragma unroll
         for (int p = 0; p < kPend; ++p) {
-            if (p >= n_pend || !pend.last[p]) continue;
-            const int nc = pend.n_chunks[p], p0 = pend.first_part[p], pair = pend.pair[p];
-            if (p0 < 0 || p0 + nc > a.n_parts) continue;
+            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
+            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p], pair = pend.pair[p];
             float m_star = -INFINITY, l_star = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
             for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
-                if (c0 > 0) {   // a pair in more than kMergeBatch pieces: fetch the next batch
+                if (c0 > 0) {   // more than kMergeBatch partials: fetch the next batch
 #pragma unroll
                     for (int j = 0; j < kMergeBatch; ++j) {
-                        const size_t pg = static_cast<size_t>(p0 + min(c0 + j, nc - 1)) * G + g;
+                        const size_t pg = static_cast<size_t>(p0 + st * min(c0 + j, nc - 1)) * G + g;
                         ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
                         o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
                         o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
@@ -237,6 +239,15 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
                 }
                 m_star = m_new;
             }
+            if (DEEP && pend.role[p] == kRoleGroup) {  // the group's partial, in the slot of its first piece
+                const size_t pg = static_cast<size_t>(p0) * G + g;
+                publish_f32x4(a.part_o + pg * D + d, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                if (d == 0) {
+                    publish_f32(a.part_ml + pg * 2 + 0, m_star);
+                    publish_f32(a.part_ml + pg * 2 + 1, l_star);
+                }
+                continue;
+            }
             const int b = pair / a.Hkv, h = pair % a.Hkv;
             const size_t orow = out_row(a, b, h, g);
             const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
@@ -245,8 +256,71 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         }
     }
-    if (threadIdx.x < n_pend && pend.last[threadIdx.x])   // ready for the next call on this workspace
-        __hip_atomic_store(a.arrivals + pend.pair[threadIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// DEEP: the plan has a pair in kDeepFrom pieces or more.  Without it the group code is not even compiled
+// in: on the headline workload its mere presence cost 0.8 us per launch (longer cold code on the
+// critical tail, more registers in the main loop).
+template <int D, int G, bool DEEP>
+__device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<D, G> &pend, int &n_pend)
+{
+    __syncthreads();
+    for (int p = 0; p < n_pend; ++p) {
+        const size_t base = static_cast<size_t>(pend.part[p]) * G;
+        for (int idx = threadIdx.x; idx < G * D / 4; idx += kThreads)
+            publish_f32x4(a.part_o + base * D + idx * 4, *reinterpret_cast<const float4 *>(&pend.o[p][idx * 4]));
+        if (threadIdx.x < G * 2) publish_f32(a.part_ml + base * 2 + threadIdx.x, pend.ml[p][threadIdx.x]);
+    }
+    drain_vmem();                                      // this thread's stores have reached the shared level ...
+    __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
+    // Round 0: every pending piece counts in (a piece of a deeply cut pair on its group's counter) and
+    // the last arrivals merge.  Round 1, only if this workgroup merged a group: that group counts in on
+    // the pair's counter.  One copy of the merge code serves both rounds: the hand-over runs once per
+    // workgroup, on cold instruction-cache lines, so its length is paid for in full.
+    for (int round = 0; round < (DEEP ? 2 : 1); ++round) {
+        if (threadIdx.x < n_pend) {
+            const int p = threadIdx.x;
+            const int nc = pend.n_chunks[p], p0 = pend.first_part[p], chunk = pend.part[p] - p0;
+            const bool ok = p0 >= 0 && chunk >= 0 && chunk < nc && p0 + nc <= a.n_parts;
+            // two levels only if every group of the pair has a counter
+            const bool deep = DEEP && nc >= kDeepFrom && static_cast<int64_t>(p0) + (nc - 1) / kGroup < a.n_group_counters;
+            int role = kRoleNone;
+            if (round == 0 && ok && !deep) {
+                if (__hip_atomic_fetch_add(a.arrivals + pend.pair[p], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nc - 1)
+                    role = kRoleFinal;
+                pend.src_first[p] = p0;
+                pend.src_stride[p] = 1;
+                pend.src_count[p] = nc;
+            } else if (round == 0 && ok) {
+                const int k = chunk / kGroup, gs = min(kGroup, nc - k * kGroup);
+                if (__hip_atomic_fetch_add(a.group_arrivals + p0 + k, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gs - 1)
+                    role = kRoleGroup;
+                pend.src_first[p] = p0 + k * kGroup;
+                pend.src_stride[p] = 1;
+                pend.src_count[p] = gs;
+            } else if (round == 1 && pend.role[p] == kRoleGroup) {
+                const int ng = (nc + kGroup - 1) / kGroup;
+                __hip_atomic_store(a.group_arrivals + p0 + chunk / kGroup, 0, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);      // the group's counter: ready for the next call
+                if (__hip_atomic_fetch_add(a.arrivals + pend.pair[p], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ng - 1)
+                    role = kRoleFinal;
+                pend.src_first[p] = p0;
+                pend.src_stride[p] = kGroup;
+                pend.src_count[p] = ng;
+            }
+            pend.role[p] = role;
+        }
+        __syncthreads();
+        merge_round<D, G, DEEP>(a, pend, n_pend);
+        bool any_group = false;
+        if (DEEP)
+            for (int p = 0; p < n_pend; ++p) any_group |= pend.role[p] == kRoleGroup;
+        if (threadIdx.x < n_pend && pend.role[threadIdx.x] == kRoleFinal)   // ready for the next call on this workspace
+            __hip_atomic_store(a.arrivals + pend.pair[threadIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!any_group) break;                             // uniform: the roles are in LDS
+        drain_vmem();                                      // the group partials are acknowledged ...
+        __syncthreads();                                   // ... all of them, before the groups count in
+    }
     n_pend = 0;
     drain_vmem();     // the compiler stops tracking the loads above: no guard waits on their registers later on
     __syncthreads();
@@ -258,7 +332,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
 //   m* = max_w m_w,  l* = sum_w l_w 2^(m_w - m*),  o* = sum_w o_w 2^(m_w - m*).
 // An item that is a whole pair writes out = o*/l* and lse.  An item of a cut pair leaves its
 // partial (m*, l*, o*) in `pend`.  Ends with a barrier, so st_o/st_ml may be reused at once.
-template <int D, int G>
+template <int D, int G, bool DEEP>
 __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
                                               const float *st_ml, PendingParts<D, G> &pend, int &n_pend)
 {
@@ -313,7 +387,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
         }
         ++n_pend;
         if (n_pend == pend_slots(D, G)) {
-            flush_pending<D, G>(a, pend, n_pend);
+            flush_pending<D, G, DEEP>(a, pend, n_pend);
             return;
         }
     }

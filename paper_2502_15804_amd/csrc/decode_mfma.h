@@ -105,7 +105,7 @@ struct ItemSlot {
 static_assert(sizeof(ItemSlot) == 48, "item table entry");
 constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches 32); longer slot lists go in batches
 
-template <int D, int G>
+template <int D, int G, bool DEEP>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
@@ -431,11 +431,11 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     st_ml[(wave * G + l16) * 2 + 1] = l_run;
                 }
             }
-            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G>(a, it, st_o, st_ml, pend, n_pend);
+            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G, DEEP>(a, it, st_o, st_ml, pend, n_pend);
         }
         wait_vmcnt<0>();   // nothing of this batch may still be landing in the rings
     }
-    if (n_pend > 0) flush_pending<D, G>(a, pend, n_pend);
+    if (n_pend > 0) flush_pending<D, G, DEEP>(a, pend, n_pend);
 }
 
 }  // namespace fairkv

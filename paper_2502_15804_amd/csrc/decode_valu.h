@@ -174,9 +174,9 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
             st_ml[(wave * G + g) * 2 + 1] = l_lane[g];
         }
     }
-    item_epilogue<D, G>(a, it, st_o, st_ml, pend, n_pend);
+    item_epilogue<D, G, true>(a, it, st_o, st_ml, pend, n_pend);
     }   // items of the slot
-    if (n_pend > 0) flush_pending<D, G>(a, pend, n_pend);
+    if (n_pend > 0) flush_pending<D, G, true>(a, pend, n_pend);
 }
 
 }  // namespace fairkv

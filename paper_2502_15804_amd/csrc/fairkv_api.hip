@@ -37,16 +37,16 @@ hipError_t launch_valu(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool DEEP>
 hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
 {
     const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
     switch (G) {
-    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8>), grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1, DEEP>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2, DEEP>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4, DEEP>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8, DEEP>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16, DEEP>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -73,15 +73,24 @@ size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
-// Workspace layout: arrivals [n_pairs] i32 | part_ml [n_parts][G][2] f32 | part_o [n_parts][G][D] f32,
-// each region starting on a 256-byte boundary.  The counters come first so that their place does
-// not depend on n_parts: calls with different plans may then share one workspace.
+// Workspace layout: counters | part_ml [n_parts][G][2] f32 | part_o [n_parts][G][D] f32, each region
+// starting on a 256-byte boundary.  The counters come first so that their place does not depend on
+// n_parts: calls with different plans may then share one workspace.
+// Counters of the hand-over: one per pair, then one per group of a pair cut into many pieces (indexed
+// by the pair's first partial slot plus the group; a line cut has fewer partial slots than pairs plus
+// slots, so n_pairs + FAIRKV_MAX_SLOTS counters serve every such plan).  Their number depends on the
+// pairs alone, so that calls with different plans can share a workspace.
+extern "C" size_t fairkv_workspace_counter_bytes(int32_t n_pairs)
+{
+    if (n_pairs < 1) return 0;
+    return align256((2 * static_cast<size_t>(n_pairs) + FAIRKV_MAX_SLOTS) * sizeof(int32_t));
+}
+
 extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D)
 {
     if (n_parts < 0 || n_pairs < 1 || G < 1 || D < 1) return 0;
     return align256(static_cast<size_t>(n_parts) * G * D * sizeof(float)) +
-           align256(static_cast<size_t>(n_parts) * G * 2 * sizeof(float)) +
-           align256(static_cast<size_t>(n_pairs) * sizeof(int32_t));
+           align256(static_cast<size_t>(n_parts) * G * 2 * sizeof(float)) + fairkv_workspace_counter_bytes(n_pairs);
 }
 
 extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
@@ -111,8 +120,10 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
     if (slot_ptr[0] != 0 || slot_ptr[n_slots] != n_items) return FAIRKV_EINVAL;
     for (int32_t j = 0; j < n_slots; ++j)
         if (slot_ptr[j] > slot_ptr[j + 1]) return FAIRKV_EINVAL;
+    bool deep = false;      // a pair in very many pieces: the kernel with the two-level merge
     for (int32_t i = 0; i < n_items; ++i) {
         const fairkv_item &it = items_host[i];
+        deep |= it.n_chunks >= kDeepFrom;
         if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
         if (it.row + it.tok_count > n_rows) return FAIRKV_EINVAL;      // the kernel reads exactly these rows of K and V
         if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
@@ -156,7 +167,9 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
         a.first_np[j] = (static_cast<uint32_t>(pair) << 8) | static_cast<uint32_t>(it.tok_count < kEarlyTok ? it.tok_count : kEarlyTok);
     }
     a.arrivals = reinterpret_cast<int32_t *>(ws);
-    ws += align256(static_cast<size_t>(B) * Hkv * sizeof(int32_t));
+    a.group_arrivals = a.arrivals + static_cast<size_t>(B) * Hkv;
+    a.n_group_counters = B * Hkv + FAIRKV_MAX_SLOTS;
+    ws += fairkv_workspace_counter_bytes(B * Hkv);
     a.part_ml = reinterpret_cast<float *>(ws);
     ws += align256(static_cast<size_t>(n_parts) * cols * 2 * sizeof(float));
     a.part_o = reinterpret_cast<float *>(ws);
@@ -174,8 +187,10 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
 
     hipError_t e;
     if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())
-        e = D == 128 ? launch_mfma<128>(static_cast<int>(cols), a, n_slots, st)
-                     : launch_mfma<64>(static_cast<int>(cols), a, n_slots, st);
+        e = D == 128 ? (deep ? launch_mfma<128, true>(static_cast<int>(cols), a, n_slots, st)
+                             : launch_mfma<128, false>(static_cast<int>(cols), a, n_slots, st))
+                     : (deep ? launch_mfma<64, true>(static_cast<int>(cols), a, n_slots, st)
+                             : launch_mfma<64, false>(static_cast<int>(cols), a, n_slots, st));
     else if (in_dtype == FAIRKV_BF16)
         e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_slots, st);
     else

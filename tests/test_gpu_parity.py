@@ -33,7 +33,7 @@ def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison
         if poison:
             layer.out.fill_(float("nan"))
             layer.lse.fill_(float("nan"))
-            counters = -(-lens.size * 4 // 256) * 256          # the first region of the workspace
+            counters = F.fairkv_workspace_counter_bytes(lens.size)          # the first region of the workspace
             layer.workspace[counters:].fill_(0xFF)
         layer.run()
         torch.cuda.synchronize()
@@ -337,3 +337,23 @@ def test_several_new_tokens_argument_checks():
     with pytest.raises(F.FairKVError) as e:                       # fp32 inputs take the single-token path only
         DecodeLayer(torch.randn((1, 2, 2, 64)).cuda(), k32.cuda(), v32.cuda(), off, lens, w32.scale).run()
     assert e.value.code == F.FAIRKV_EUNSUPPORTED
+
+
+def test_pairs_cut_into_very_many_pieces_are_merged_in_two_levels():
+    """Long heads, few of them, many slots: pairs in 32 ... 80 pieces, merged group by group.  Several
+    calls in a row on one workspace: every counter is back at zero after each."""
+    F = _F()
+    rng = np.random.default_rng(11)
+    for B, Hkv, G, n_slots, lens_ in ((1, 2, 8, 256, [[16384, 3000]]), (2, 1, 4, 160, [[9000], [700]]),
+                                      (1, 3, 2, 256, [[2049, 17, 12000]])):
+        lens = np.array(lens_, np.int32)
+        w, off, q, k, v = make_case(B, Hkv * G, Hkv, 128, "bf16", lens, seed=int(rng.integers(1 << 20)), gap_rows=1)
+        err, layer = check(w, q, k, v, off, lens, policy=3, n_slots=n_slots, min_chunk=32, overhead_tokens=16, calls=3)
+        assert layer.plan.items["n_chunks"].max() >= 32
+        nb = F.fairkv_workspace_counter_bytes(B * Hkv)
+        assert int(layer.workspace[:nb].view(torch.int32).abs().sum().item()) == 0
+    # equal shares with a tiny cap on the counter index: the pair falls back to one level
+    lens = np.array([[5000, 5000, 5000]], np.int32)
+    w, off, q, k, v = make_case(1, 6, 3, 64, "bf16", lens, seed=5)
+    err, layer = check(w, q, k, v, off, lens, policy=2, n_slots=64, min_chunk=32, oversub=4, calls=2)
+    assert layer.plan.items["n_chunks"].max() > 8
