@@ -128,7 +128,7 @@ struct Geo {
 };
 
 
-constexpr int kMergeBatch = 4;   // partials of a cut pair fetched at once by the merging workgroup
+constexpr int kMergeBatch = 8;   // partials of a cut pair fetched at once by the merging workgroup
 
 // Two floats fetched as one 8-byte agent-scope load (see publish_f32 / fetch_f32 above).
 __device__ __forceinline__ float2 fetch_f32x2(const float *p)
@@ -141,7 +141,10 @@ __device__ __forceinline__ float2 fetch_f32x2(const float *p)
 // wait in LDS until the slot's list is done (or the buffer is full) and are then published
 // together, so that the hand-over, which costs several memory round trips, happens once per
 // workgroup and not in the middle of the stream.
-constexpr int pend_slots(int D, int G) { return D * G > 1024 ? 2 : 3; }   // LDS is the limit
+// Two: a line cut leaves a slot at most two pieces of cut pairs (its first and its last item).  A third
+// slot made the hand-over code half as long again, and that code runs cold on the critical tail:
+// 0.15 us per launch on the headline workload.
+constexpr int pend_slots(int, int) { return 2; }
 
 template <int D, int G>
 struct PendingParts {
@@ -198,10 +201,14 @@ __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D,
             const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
-                const size_t pg = static_cast<size_t>(p0 + st * min(j, nc - 1)) * G + g;   // past the end: weight 0 below
-                ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
-                o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
-                o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                ml[p][j] = make_float2(-INFINITY, 0.f);        // past the end: weight 0 below, and no load
+                o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
+                if (j < nc) {
+                    const size_t pg = static_cast<size_t>(p0 + st * j) * G + g;
+                    ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                    o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                    o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                }
             }
         }
 #pragma unroll
@@ -213,10 +220,14 @@ __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D,
                 if (c0 > 0) {   // more than kMergeBatch partials: fetch the next batch
 #pragma unroll
                     for (int j = 0; j < kMergeBatch; ++j) {
-                        const size_t pg = static_cast<size_t>(p0 + st * min(c0 + j, nc - 1)) * G + g;
-                        ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
-                        o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
-                        o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                        ml[p][j] = make_float2(-INFINITY, 0.f);
+                        o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
+                        if (c0 + j < nc) {
+                            const size_t pg = static_cast<size_t>(p0 + st * (c0 + j)) * G + g;
+                            ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                            o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                            o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                        }
                     }
                 }
                 float m_new = m_star;
