@@ -122,6 +122,42 @@ def attention_multi(q, k, v, off, lens, scale, n_threads=0):
     return out, lse
 
 
+def decode_e4m3fn(codes):
+    """Values of 8-bit floats in the OCP E4M3 format ("FN": finite, no infinities), written out from the
+    format's definition: 1 sign bit, 4 exponent bits with bias 7, 3 mantissa bits; exponent field 0 holds
+    the subnormals m/8 * 2^-6; the all-ones code S.1111.111 is NaN; everything else is (1 + m/8) * 2^(e-7),
+    up to 448.  codes: uint8 array; returns float64 of the same shape."""
+    table = np.empty(256, dtype=np.float64)
+    for c in range(256):
+        sign = -1.0 if c & 0x80 else 1.0
+        e, mant = (c >> 3) & 0xF, c & 0x7
+        if e == 0xF and mant == 0x7:
+            table[c] = np.nan
+        elif e == 0:
+            table[c] = sign * (mant / 8.0) * 2.0 ** -6
+        else:
+            table[c] = sign * (1.0 + mant / 8.0) * 2.0 ** (e - 7)
+    codes = np.asarray(codes)
+    if codes.dtype != np.uint8:
+        raise TypeError("codes must be uint8")
+    return table[codes]
+
+
+def attention_kv8(q, k8, v8, off, lens, scale, k_scale, v_scale, n_threads=0):
+    """The same attention over a cache stored as 8-bit floats (E4M3) with one scale factor for K and
+    one for V: K = k_scale * decode(k8), V = v_scale * decode(v8), everything else in fp64.
+    q: bf16 bit patterns (uint16), [B,Hq,D] or [B,q_len,Hq,D]; k8, v8: uint8 [rows,D]."""
+    q = np.ascontiguousarray(q)
+    if q.dtype != np.uint16:
+        raise TypeError("q must be bf16 bit patterns (uint16)")
+    q64 = (q.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    k64 = decode_e4m3fn(k8) * float(k_scale)
+    v64 = decode_e4m3fn(v8) * float(v_scale)
+    if q.ndim == 4:
+        return attention_multi(q64, k64, v64, off, lens, scale, n_threads=n_threads)
+    return attention(q64, k64, v64, off, lens, scale, n_threads=n_threads)
+
+
 def attention_chunk(q, k, v, b, hq, row0, n, scale):
     """(m, l, acc[D]) of rows [row0, row0+n) of K/V for query q[b, hq]."""
     q, k, v, dt = _check_inputs(q, k, v)

@@ -331,3 +331,47 @@ def test_multi_token_queries_are_single_token_queries_over_shorter_caches():
     assert np.array_equal(o1[:, 0], ro) and np.array_equal(l1[:, 0], rl)        # q_len = 1 is the plain path
     with pytest.raises(ValueError):
         OA.attention_multi(q[:, 0], k, v, off, lens, 0.4)
+
+
+# ---- a cache stored as 8-bit floats ------------------------------------------------------------
+def test_e4m3_decoding_against_an_independent_converter_and_known_values():
+    torch = pytest.importorskip("torch")
+    codes = np.arange(256, dtype=np.uint8)
+    got = OA.decode_e4m3fn(codes)
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).double().numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
+    assert got[0x38] == 1.0 and got[0x7e] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+    assert got[0xb8] == -1.0 and got[0x00] == 0.0 and np.signbit(got[0x80]) and np.isnan(got[[0x7f, 0xff]]).all()
+    assert (np.diff(got[:0x7f]) > 0).all()                 # the positive codes are ordered like their values
+    with pytest.raises(TypeError):
+        OA.decode_e4m3fn(np.arange(4))
+
+
+def test_kv8_attention_is_attention_over_the_dequantised_cache():
+    rng = np.random.default_rng(31)
+    B, Hkv, G, D = 2, 2, 2, 8
+    lens = rng.integers(0, 20, size=(B, Hkv)).astype(np.int32)
+    off = np.arange(B * Hkv, dtype=np.int64).reshape(B, Hkv) * 24
+    k8 = rng.integers(0, 0x78, size=(B * Hkv * 24, D)).astype(np.uint8)      # finite codes only
+    v8 = (rng.integers(0, 0x78, size=(B * Hkv * 24, D)) | (rng.integers(0, 2, size=(B * Hkv * 24, D)) << 7)).astype(np.uint8)
+    qf = rng.normal(size=(B, Hkv * G, D)).astype(np.float32)
+    qbits = (qf.view(np.uint32) >> 16).astype(np.uint16)                     # truncated to bf16: any bf16 will do
+    out, lse = OA.attention_kv8(qbits, k8, v8, off, lens, 0.3, 0.5, 0.25)
+    q64 = (qbits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    for b in range(B):
+        for hq in range(Hkv * G):
+            h = hq // G
+            n, r0 = int(lens[b, h]), int(off[b, h])
+            if n == 0:
+                assert (out[b, hq] == 0).all() and np.isneginf(lse[b, hq])
+                continue
+            kk = OA.decode_e4m3fn(k8[r0:r0 + n]) * 0.5
+            vv = OA.decode_e4m3fn(v8[r0:r0 + n]) * 0.25
+            s = kk @ q64[b, hq] * 0.3
+            w = np.exp(s - s.max())
+            assert np.abs(out[b, hq] - (w @ vv) / w.sum()).max() < 1e-12
+            assert abs(lse[b, hq] - (s.max() + np.log(w.sum()))) < 1e-12
+    # scaling K by 2 and halving the score scale changes nothing; scaling V scales the output
+    o2, l2 = OA.attention_kv8(qbits, k8, v8, off, lens, 0.15, 1.0, 0.5)
+    live = lens.repeat(G, axis=1) > 0
+    assert np.allclose(o2[live], 2 * out[live], rtol=1e-12, atol=0) and np.allclose(l2[live], lse[live], rtol=1e-12, atol=1e-12)
