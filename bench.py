@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--q-len", type=int, default=1,
                     help="new tokens per sequence in one call (fairkv_decode_attn_multi): 8 heads x 2 tokens fill the "
                          "16 columns of a matrix-core tile; K and V are still streamed once")
+    ap.add_argument("--kv-dtype", choices=("bf16", "fp8"), default="bf16",
+                    help="fp8: the same workload with K and V stored as E4M3 bytes (fairkv_decode_attn_kv8); a side "
+                         "measurement, never the headline")
     ap.add_argument("--latency-model", action="store_true",
                     help="instead of the benchmark: decode latency of one Llama-70B-shaped layer against batch size "
                          "and against a uniform per-head budget (the paper's Section 3.2 / Figure 2 experiment), "
@@ -60,10 +63,16 @@ def parse():
     return ap.parse_args()
 
 
+KV8_PLAN_DEFAULTS = {"tile": 32, "min_chunk": 64, "overhead_tokens": 256}
+
+
 class Rotation:
     """Distinct layer buffers of one workload, resident on the GPU, with their plans."""
 
-    def __init__(self, name, n_layers, seed, policy, overrides, q_len=1):
+    K_SCALE, V_SCALE = 0.02, 0.03      # per-tensor scales of the 8-bit variant (N(0,1) data: well inside +-448)
+
+    def __init__(self, name, n_layers, seed, policy, overrides, q_len=1, kv8=False):
+        import numpy as np
         import torch
         import workloads as W
         import paper_2502_15804_amd as F
@@ -90,12 +99,15 @@ class Rotation:
             if q_len > 1:       # q_len new tokens per sequence; their K/V are the last rows of every pair already
                 gq = torch.Generator(device="cuda").manual_seed(1000 * seed + li)
                 q = torch.randn((self.w.B, q_len, self.w.Hq, self.w.D), generator=gq, device="cuda").to(q.dtype)
+            if kv8:
+                k, v = W.make_kv8(self.w, total, self.K_SCALE, self.V_SCALE, seed=seed, layer=li, device="cuda")
             self.layers.append(DecodeLayer(q, k, v, off, lens, self.w.scale, params=self.params,
-                                           workspace=self.workspace))
+                                           workspace=self.workspace, k_scale=self.K_SCALE, v_scale=self.V_SCALE))
             self.lens.append(lens)
             self.offs.append(off)
             self.bytes.append(W.algorithmic_bytes(self.w, lens) + (q_len - 1) * self.w.B * self.w.Hq * self.w.D *
-                              (self.w.elem_bytes + 4))
+                              (self.w.elem_bytes + 4)
+                              - (int(lens.astype(np.int64).sum()) * self.w.D * 2 * (self.w.elem_bytes - 1) if kv8 else 0))
         self.plan_us = 1e6 * sorted(plan_times)[len(plan_times) // 2]
         torch.cuda.synchronize()
 
@@ -169,8 +181,12 @@ def spot_check(rot, n_layers=2, n_samples=48):
     for li in sorted({0, len(rot.layers) - 1, len(rot.layers) // 2})[:max(1, n_layers + 1)]:
         layer = rot.layers[li]
         sel = rng.choice(rot.w.B * rot.w.Hq, size=min(n_samples, rot.w.B * rot.w.Hq), replace=False).astype(np.int32)
-        bits = [W.to_numpy_bits(t) for t in (layer.q, layer.k, layer.v)]
         got = layer.out.float().cpu().numpy().astype(np.float64).reshape(-1, rot.w.D)
+        if layer.kv8:            # every output of one layer: the oracle decodes the whole cache anyway
+            ro, _ = OA.attention_kv8(W.to_numpy_bits(layer.q), layer.k.cpu().numpy(), layer.v.cpu().numpy(), rot.offs[li],
+                                     rot.lens[li], rot.w.scale, layer.k_scale, layer.v_scale)
+            return float(np.abs(got - ro.reshape(-1, rot.w.D)).max())
+        bits = [W.to_numpy_bits(t) for t in (layer.q, layer.k, layer.v)]
         if layer.q_len > 1:      # every output: the oracle for several new tokens has no selection list
             ro, _ = OA.attention_multi(*bits, rot.offs[li], rot.lens[li], rot.w.scale)
             worst = max(worst, float(np.abs(got - ro.reshape(-1, rot.w.D)).max()))
@@ -513,7 +529,12 @@ def main():
     n_layers = a.layers or w.n_layers
     overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens")
                  if getattr(a, k) is not None}
-    rot = Rotation(a.workload, n_layers, a.seed, a.policy, overrides, a.q_len)
+    kv8 = a.kv_dtype == "fp8"
+    if kv8:
+        a.no_extras = True      # the comparisons and the CPU baseline belong to the headline configuration
+        # half the bytes per token: the planner's per-item overhead is worth twice the tokens, and a step is 32 tokens
+        overrides = {**KV8_PLAN_DEFAULTS, **overrides}
+    rot = Rotation(a.workload, n_layers, a.seed, a.policy, overrides, a.q_len, kv8)
     host_s, ev_s, moved = timed(rot, a.steps, a.warmup, not a.no_graph)
     gbs = moved / ev_s / 1e9
     ms_step = 1e3 * ev_s / a.steps
@@ -527,7 +548,7 @@ def main():
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.description}", "storage": w.dtype, "B": w.B, "q_len": a.q_len, "Hq": w.Hq, "Hkv": w.Hkv,
+        "config": {"workload": f"{w.name}: {w.description}", "storage": "e4m3 K/V, bf16 q" if kv8 else w.dtype, "B": w.B, "q_len": a.q_len, "Hq": w.Hq, "Hkv": w.Hkv,
                    "D": w.D, "layers_rotated": n_layers, "rotation_GB": round(sum(rot.bytes) / 1e9, 3),
                    "policy": a.policy, "n_slots": int(rot.params.n_slots), "min_chunk": int(rot.params.min_chunk),
                    "oversub": int(rot.params.oversub), "graph_replay": not a.no_graph,
@@ -537,8 +558,8 @@ def main():
         "plan_host_us_per_layer": round(rot.plan_us, 1),
         "plan_layer0": {"max_slot_load": loads_max, "min_slot_load": loads_min, "efficiency_E": round(eff0, 4)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(a.workload),
-                     "kernel": f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}>",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None if kv8 else measured_traffic(a.workload),
+                     "kernel": f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}{', KV8' if kv8 else ''}>",
                      "bytes_per_launch": round(moved / a.steps), "us_per_launch": round(1e3 * ms_step, 3)},
         "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
                          "(Llama-3.3-70B, Section 5.2.2); other hardware, not this metric",

@@ -24,7 +24,7 @@ FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_workspace_counter_bytes",
            "fairkv_decode_attn",
-           "fairkv_decode_attn_multi",
+           "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
@@ -109,6 +109,10 @@ def lib() -> ctypes.CDLL:
         L.fairkv_decode_attn_multi.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp,
                                                ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                                ctypes.c_float, vp]
+        L.fairkv_decode_attn_kv8.restype = ctypes.c_int
+        L.fairkv_decode_attn_kv8.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_float, ctypes.c_float, vp, vp, i32, vp,
+                                             i32, i32, vp, ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32,
+                                             ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -270,6 +274,50 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
         ctypes.c_void_p(stream.cuda_stream))
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_decode_attn_multi" if q_len > 1 else "fairkv_decode_attn")
+
+
+def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_ptr, n_parts, workspace, out, lse,
+                           scale, Hkv, stream=None):
+    """fairkv_decode_attn over a cache stored as 8-bit floats (E4M3, finite-only "fn" encoding).
+
+    k8, v8 [rows,D]: torch.float8_e4m3fn or uint8 holding the same bytes; a stored byte stands for
+    value * k_scale (v_scale).  q [B,Hq,D] or [B,q_len,Hq,D] bfloat16, D = 128.  Everything else as in
+    fairkv_decode_attn.
+    """
+    import torch
+
+    if q.dim() == 4:
+        B, q_len, Hq, D = q.shape
+    else:
+        (B, Hq, D), q_len = q.shape, 1
+    dt = {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}
+    bytes_ok = (torch.uint8, torch.float8_e4m3fn)
+    if q.dtype != torch.bfloat16 or k8.dtype not in bytes_ok or v8.dtype not in bytes_ok or out.dtype not in dt:
+        raise TypeError("q must be bf16, k8/v8 float8_e4m3fn or uint8, out bf16 or fp32")
+    _check_dev(q=q, k8=k8, v8=v8, items=items, workspace=workspace, out=out, lse=lse)
+    if not isinstance(slot_ptr, np.ndarray) or slot_ptr.dtype != np.int32 or not slot_ptr.flags.c_contiguous:
+        raise TypeError("slot_ptr must be a contiguous host int32 array")
+    if lse is not None and lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    if k8.dim() != 2 or k8.shape[1] != D or v8.shape != k8.shape or tuple(out.shape) != tuple(q.shape) or slot_ptr.size < 2:
+        raise ValueError("shape mismatch")
+    if lse is not None and tuple(lse.shape) != tuple(q.shape[:-1]):
+        raise ValueError("lse must have q's shape without the last dimension")
+    item_bytes = items.numel() * items.element_size()
+    if item_bytes % 32 != 0:
+        raise ValueError("items must be a whole number of 32-byte records")
+    if (not isinstance(items_host, np.ndarray) or items_host.dtype != ITEM_DTYPE or not items_host.flags.c_contiguous
+            or items_host.size * 32 != item_bytes):
+        raise TypeError("items_host must be the plan's contiguous item array, as many records as `items`")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    rc = lib().fairkv_decode_attn_kv8(
+        _ptr(q), _ptr(k8), _ptr(v8), k8.shape[0], float(k_scale), float(v_scale), _ptr(items), items_host.ctypes.data,
+        item_bytes // 32, slot_ptr.ctypes.data, slot_ptr.size - 1, int(n_parts), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, dt[out.dtype],
+        float(scale), ctypes.c_void_p(stream.cuda_stream))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_decode_attn_kv8")
 
 
 def _dtype_code(t):

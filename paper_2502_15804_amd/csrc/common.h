@@ -97,14 +97,16 @@ struct DecodeArgs {
     int32_t q_len, g_shift;     // new tokens per sequence; log2 of the query heads per KV head.  A kernel's
                                 // template parameter G counts columns: q_len * (1 << g_shift), column
                                 // c = new token (c >> g_shift), head (c & mask) of the group
-    float scale_log2;           // scale * log2(e): scores are kept in log2 units so exp is one v_exp_f32
+    float scale_log2;           // scale * log2(e) (times the K scale of an 8-bit cache): scores are kept in log2
+                                // units so exp is one v_exp_f32
+    float v_scale;              // 1, or the V scale of an 8-bit cache: multiplies out
     // What a workgroup needs before it has read anything from memory, riding in the kernel arguments:
     int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1])
     uint32_t first_row[FAIRKV_MAX_SLOTS];     // first K/V row of slot j's first item ...
-    uint32_t first_np[FAIRKV_MAX_SLOTS];      // ... its pair b*Hkv+h in bits 8..31 and min(tok_count, kEarlyTok) in
-                                              // bits 0..7; 0 = no early start for this slot
+    uint32_t first_np[FAIRKV_MAX_SLOTS];      // ... its pair b*Hkv+h in bits 9..31 and min(tok_count, kEarlyTok) in
+                                              // bits 0..8; 0 = no early start for this slot
 };
-constexpr int kEarlyTok = 192;            // tokens of a slot's first item that the early start may request
+constexpr int kEarlyTok = 256;            // tokens of a slot's first item that the early start may request
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
 __device__ __forceinline__ size_t out_row(const DecodeArgs &a, int b, int h, int c)
@@ -261,7 +263,7 @@ __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D,
             }
             const int b = pair / a.Hkv, h = pair % a.Hkv;
             const size_t orow = out_row(a, b, h, g);
-            const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
             store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             if (d == 0 && a.lse)
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
@@ -377,7 +379,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
         }
         if (whole_pair) {
             const size_t orow = out_row(a, b, h, g);
-            const float inv = l_star > 0.f ? 1.f / l_star : 0.f;
+            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
             store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
             if (d == 0 && a.lse)
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;

@@ -41,6 +41,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(4))) short i16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(8))) float f32x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
+typedef __attribute__((ext_vector_type(2))) int i32x2_t;
 
 constexpr int kTok = 16;      // tokens per tile (the M of the score MFMA, the K of the PV MFMA)
 constexpr int kStages = 2;    // tiles per wave resident in LDS: one being consumed, the others in flight (3 measured no faster)
@@ -94,6 +97,17 @@ __device__ __forceinline__ int64_t uniform64(int64_t x)   // a wave-uniform valu
     return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
+// Eight E4M3 bytes widened to eight bf16 (exact; v_cvt_scalef32_pk_bf16_fp8 with scale 1 takes two bytes
+// at a time: the low or the high half of a dword).
+__device__ __forceinline__ bf16x8_t widen8(uint2 w)
+{
+    const bf16x2_v a0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, false);
+    const bf16x2_v a1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, true);
+    const bf16x2_v a2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, false);
+    const bf16x2_v a3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, true);
+    return bf16x8_t{a0[0], a0[1], a1[0], a1[1], a2[0], a2[1], a3[0], a3[1]};
+}
+
 // LDS copy of the slot's items: what the waves need of a fairkv_item, plus the checked length.
 struct ItemSlot {
     int64_t row;
@@ -105,24 +119,38 @@ struct ItemSlot {
 static_assert(sizeof(ItemSlot) == 48, "item table entry");
 constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches 32); longer slot lists go in batches
 
-template <int D, int G, bool DEEP>
+// KV8: K and V are stored as 8-bit floats (E4M3), one byte per element, and widened to bf16 in registers
+// (exactly: every E4M3 value is a bf16 value), so the arithmetic is that of the bf16 path.  A row is half as
+// long, so a stage holds 32 tokens instead of 16 in the same 8 KB, and a step works on two 16-token score
+// tiles and one 32-token P.V product:
+//     S^T = K . q^T    2 x 4 x mfma_16x16x32 on K widened 8 bytes at a time
+//     O^T += V^T . P   8 x mfma_16x16x32; the contraction index k = 8 lq + r of a lane stands for token
+//                      4 lq + r of the first score tile (r < 4) or of the second (r >= 4), which is how the
+//                      lane's own eight weights are laid out already; V^T comes out of the LDS through the
+//                      8-bit transposing read: lane i of a 16-lane group addresses the 8 bytes (token
+//                      t_(i/2), columns 8 (i%2) .. +7) and lane j receives byte j%8 of the fragments
+//                      j/8, j/8 + 2, ..., i.e. column j of tokens t_0 .. t_7 (layout checked on the GPU).
+template <int D, int G, bool DEEP, bool KV8>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
+    static_assert(!KV8 || D == 128, "8-bit caches: head_dim 128 only");
     static_assert(G >= 1 && G <= 16, "query heads of a group fit the N dimension");
+    constexpr int TOK = KV8 ? 2 * kTok : kTok;          // tokens per stage and per step
     constexpr int kEarly = kStages < 3 ? kStages : 3;   // tiles per wave the early start may request
-    static_assert(kStages >= 2 && kStages <= 4 && kEarlyTok >= kEarly * kWaves * kTok && kEarlyTok < 256, "ring, early start");
+    static_assert(kStages >= 2 && kStages <= 4 && kEarlyTok >= kEarly * kWaves * TOK && kEarlyTok < 512, "ring, early start");
     static_assert(sizeof(fairkv_item) == 32, "two 16-byte pieces per item");
-    constexpr int ROWB = D * 2;              // bytes per K, V or q row
+    constexpr int QROWB = D * 2;             // bytes per q row (bf16)
+    constexpr int ROWB = KV8 ? D : D * 2;    // bytes per K or V row
     constexpr int PPR = ROWB / 16;           // 16-byte pieces per row: 16 or 8
     constexpr int RPI = 64 / PPR;            // rows one wave-wide 16-byte load covers
-    constexpr int LPT = kTok / RPI;          // wave-wide loads per K (or V) tile
-    constexpr int TILEB = kTok * ROWB;       // bytes of one K (or V) tile
+    constexpr int LPT = TOK / RPI;           // wave-wide loads per K (or V) tile
+    constexpr int TILEB = TOK * ROWB;        // bytes of one K (or V) tile
     constexpr int STAGEB = 2 * TILEB;        // K tile then V tile
     constexpr int LOADS = 2 * LPT;           // vector-memory instructions per stage
     constexpr int NSL = D / 32;              // d slices of the score contraction
     constexpr int NDB = D / 16;              // 16-wide d blocks of the output
-    constexpr int QBYTES = G * ROWB;         // the G query rows of a group are contiguous in q
+    constexpr int QBYTES = G * QROWB;        // the G query rows of a group are contiguous in q
     constexpr int QL = (QBYTES + 1023) / 1024;   // wave-wide loads per query block
     constexpr int QBUF = QL * 1024;
 
@@ -163,32 +191,47 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // ... and where a lane reads its operands: the K row l16 (pieces 4 s + lq) and, through the
     // transposing read, 4 d's of V row 4 lq + l16/4 (lane j of a 16-lane group receives element
     // j%4 of the rows its lanes 4i + j/4 address).
-    uint32_t k_rd[NSL], v_rd[NDB];
+    // (8-bit caches: 8 bytes of K row l16 or 16 + l16 at byte 32 s + 8 lq; for V the fragment this
+    // lane addresses in the transposing read, see above.)
+    constexpr int NKR = KV8 ? 2 * NSL : NSL;
+    uint32_t k_rd[NKR], v_rd[NDB];
+    if constexpr (!KV8) {
 #pragma unroll
-    for (int s = 0; s < NSL; ++s) k_rd[s] = l16 * ROWB + ((4 * s + lq) ^ (l16 % PPR)) * 16;
-    {
+        for (int s = 0; s < NSL; ++s) k_rd[s] = l16 * ROWB + ((4 * s + lq) ^ (l16 % PPR)) * 16;
         const int vrow = 4 * lq + (l16 >> 2), vsub = l16 & 3;
 #pragma unroll
         for (int nb_ = 0; nb_ < NDB; ++nb_)
             v_rd[nb_] = TILEB + vrow * ROWB + (((2 * nb_ + (vsub >> 1)) ^ ((2 * vrow) % PPR)) * 16) + (vsub & 1) * 8;
+    } else {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int s = 0; s < NSL; ++s) {
+                const int row = 16 * u + l16;
+                k_rd[u * NSL + s] = row * ROWB + (((2 * s + (lq >> 1)) ^ (row % PPR)) * 16) + (lq & 1) * 8;
+            }
+        const int r = l16 >> 1;                                            // which of the lane group's 8 tokens
+        const int vrow = r < 4 ? 4 * lq + r : 16 + 4 * lq + (r - 4);
+#pragma unroll
+        for (int nb_ = 0; nb_ < NDB; ++nb_) v_rd[nb_] = TILEB + vrow * ROWB + ((nb_ ^ ((2 * vrow) % PPR)) * 16) + (l16 & 1) * 8;
     }
 
     // tiles of an n-token item that fall to this wave: tiles wave, wave + kWaves, ...
     auto tiles_of = [&](int n) {
-        const int n_tiles = (n + kTok - 1) / kTok;
+        const int n_tiles = (n + TOK - 1) / TOK;
         return n_tiles > wave ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     };
 
     // Fetch of this wave's t-th tile of an item into one stage: always exactly LOADS loads.
     // Rows past the end of the item re-read its last row (finite data with weight 0).
     auto fetch = [&](int64_t row, int n, int t, int stage) {
-        const int tok0 = (wave + t * kWaves) * kTok;
+        const int tok0 = (wave + t * kWaves) * TOK;
         const int last = n - 1 - tok0;
         const char *kbase = static_cast<const char *>(a.k) + (row + tok0) * ROWB;
         const char *vbase = static_cast<const char *>(a.v) + (row + tok0) * ROWB;
         const uint32_t kst = ring_lds + stage * STAGEB;
         const uint32_t vst = kst + TILEB;
-        if (last >= kTok - 1) {
+        if (last >= TOK - 1) {
 #pragma unroll
             for (int i = 0; i < LPT; ++i) {
                 load16_to_lds(kbase, k_off[i], kst + i * 1024);
@@ -210,13 +253,13 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // token are contiguous, the new tokens are Hq rows apart.
     auto fetch_q = [&](int b, int h, int buf) {
         const char *src = static_cast<const char *>(a.q) +
-                          (static_cast<size_t>(b) * a.q_len * a.Hq + (h << a.g_shift)) * ROWB;
+                          (static_cast<size_t>(b) * a.q_len * a.Hq + (h << a.g_shift)) * QROWB;
 #pragma unroll
         for (int i = 0; i < QL; ++i) {
-            const int o = min(i * 1024 + lane * 16, QBYTES - 16);      // byte o of the [G][ROWB] image in LDS
-            const int c = o / ROWB;
+            const int o = min(i * 1024 + lane * 16, QBYTES - 16);      // byte o of the [G][QROWB] image in LDS
+            const int c = o / QROWB;
             const int row = (c >> a.g_shift) * a.Hq + (c & ((1 << a.g_shift) - 1));
-            load16_to_lds(src, row * ROWB + o % ROWB, q_lds + buf * QBUF + i * 1024);
+            load16_to_lds(src, row * QROWB + o % QROWB, q_lds + buf * QBUF + i * 1024);
         }
     };
 
@@ -250,10 +293,10 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // tiles are all requested at once, before anything has come back from memory.
     fetch_items(i_begin);
     const uint32_t np0 = a.first_np[blockIdx.x];
-    const int n0 = static_cast<int>(np0 & 0xffu);
+    const int n0 = static_cast<int>(np0 & 0x1ffu);
     const bool seeded = n0 > 0;
     if (seeded) {
-        const int pair0 = static_cast<int>(np0 >> 8);
+        const int pair0 = static_cast<int>(np0 >> 9);
         f_b = pair0 / a.Hkv;
         f_h = pair0 - f_b * a.Hkv;
         f_row = a.first_row[blockIdx.x];
@@ -348,72 +391,137 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 if (t == 0) {
                     // q as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8].  Heads
                     // >= G repeat head G-1: their columns of the products are computed and never stored.
-                    const char *qsrc = q_ring + c_stage * QBUF + min(l16, G - 1) * ROWB + lq * 16;
+                    const char *qsrc = q_ring + c_stage * QBUF + min(l16, G - 1) * QROWB + lq * 16;
 #pragma unroll
                     for (int s = 0; s < NSL; ++s)
                         qb[s] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(qsrc + s * 64));
                 }
 
-                // ---- every LDS read of the tile, issued together -----------------------------------
-                const char *st = ring + c_stage * STAGEB;
-                uint4 kw[NSL];
-                i16x4_t vt[NDB];
+                if constexpr (KV8) {
+                    // ---- every LDS read of the step, issued together ---------------------------------
+                    const char *st = ring + c_stage * STAGEB;
+                    uint2 kw[NKR];
+                    i32x2_t vt[NDB];
 #pragma unroll
-                for (int s = 0; s < NSL; ++s) kw[s] = *reinterpret_cast<const uint4 *>(st + k_rd[s]);
-#pragma unroll
-                for (int nb_ = 0; nb_ < NDB; ++nb_)
-                    vt[nb_] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(st + v_rd[nb_]));
-
-                // ---- scores: S^T[token 4 lq + i][head l16], in log2 units --------------------------
-                f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < NSL; ++s)
-                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw[s]), qb[s], sacc, 0, 0, 0);
-                const int tok0 = (wave + t * kWaves) * kTok;
-                const bool masked = n - hidden_max - tok0 < kTok;    // some column does not see the whole tile
-                float sv[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * a.scale_log2;
-                if (masked) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (4 * lq + i >= n_col - tok0) sv[i] = -INFINITY;
-                }
-
-                // ---- raise the reference maximum if some score is far above it (always on the first tile)
-                float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-                if (__builtin_amdgcn_ballot_w64(mx > m_run + kBump) != 0) {
-                    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                    const float m_new = fmaxf(m_run, mx);
-                    const float alpha = m_new == m_run ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
-                    l_run *= alpha;
+                    for (int s = 0; s < NKR; ++s) kw[s] = *reinterpret_cast<const uint2 *>(st + k_rd[s]);
 #pragma unroll
                     for (int nb_ = 0; nb_ < NDB; ++nb_)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) o[nb_][i] *= alpha;
-                    m_run = m_new;
-                }
+                        vt[nb_] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                            (__attribute__((address_space(3))) i32x2_t *)FAIRKV_LDS_PTR(st + v_rd[nb_]));
 
-                // ---- weights, rounded to bf16; their sum uses the rounded values, so out is an exact
-                //      convex combination of V rows -------------------------------------------------
-                float p[4];
+                    // ---- scores of two 16-token tiles: S^T[token 16 u + 4 lq + i][head l16] ----------
+                    f32x4_t sacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_run);
-                if (masked) {     // a column that has seen nothing yet has m = -inf: its weights are 0, not exp2(nan)
+                    for (int u = 0; u < 2; ++u)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (sv[i] == -INFINITY) p[i] = 0.f;
-                }
-                const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
+                        for (int s = 0; s < NSL; ++s)
+                            sacc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(kw[u * NSL + s]), qb[s], sacc[u], 0, 0, 0);
+                    const int tok0 = (wave + t * kWaves) * TOK;
+                    const bool masked = n - hidden_max - tok0 < TOK;     // some column does not see the whole step
+                    float sv[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) l_run += static_cast<float>(pb[i]);
+                    for (int r = 0; r < 8; ++r) sv[r] = sacc[r >> 2][r & 3] * a.scale_log2;
+                    if (masked) {
+#pragma unroll
+                        for (int r = 0; r < 8; ++r)
+                            if (16 * (r >> 2) + 4 * lq + (r & 3) >= n_col - tok0) sv[r] = -INFINITY;
+                    }
 
-                // ---- O^T[d][head] += V^T P ---------------------------------------------------------
+                    // ---- raise the reference maximum if some score is far above it ------------------
+                    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+                    if (__builtin_amdgcn_ballot_w64(mx > m_run + kBump) != 0) {
+                        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                        const float m_new = fmaxf(m_run, mx);
+                        const float alpha = m_new == m_run ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+                        l_run *= alpha;
 #pragma unroll
-                for (int nb_ = 0; nb_ < NDB; ++nb_)
-                    o[nb_] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[nb_], __builtin_bit_cast(i16x4_t, pb), o[nb_], 0, 0, 0);
+                        for (int nb_ = 0; nb_ < NDB; ++nb_)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[nb_][i] *= alpha;
+                        m_run = m_new;
+                    }
+
+                    // ---- weights, rounded to bf16, in the order the contraction index wants them ------
+                    float p[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(sv[r] - m_run);
+                    if (masked) {
+#pragma unroll
+                        for (int r = 0; r < 8; ++r)
+                            if (sv[r] == -INFINITY) p[r] = 0.f;
+                    }
+                    const bf16x8_t pb = __builtin_convertvector(f32x8_t{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, bf16x8_t);
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) l_run += static_cast<float>(pb[r]);
+
+                    // ---- O^T[d][head] += V^T P over the 32 tokens ------------------------------------
+#pragma unroll
+                    for (int nb_ = 0; nb_ < NDB; ++nb_)
+                        o[nb_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            widen8(uint2{static_cast<uint32_t>(vt[nb_][0]), static_cast<uint32_t>(vt[nb_][1])}), pb, o[nb_], 0, 0, 0);
+                } else {
+                    // ---- every LDS read of the tile, issued together -----------------------------------
+                    const char *st = ring + c_stage * STAGEB;
+                    uint4 kw[NSL];
+                    i16x4_t vt[NDB];
+    #pragma unroll
+                    for (int s = 0; s < NSL; ++s) kw[s] = *reinterpret_cast<const uint4 *>(st + k_rd[s]);
+    #pragma unroll
+                    for (int nb_ = 0; nb_ < NDB; ++nb_)
+                        vt[nb_] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) i16x4_t *)FAIRKV_LDS_PTR(st + v_rd[nb_]));
+
+                    // ---- scores: S^T[token 4 lq + i][head l16], in log2 units --------------------------
+                    f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+    #pragma unroll
+                    for (int s = 0; s < NSL; ++s)
+                        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw[s]), qb[s], sacc, 0, 0, 0);
+                    const int tok0 = (wave + t * kWaves) * TOK;
+                    const bool masked = n - hidden_max - tok0 < TOK;    // some column does not see the whole tile
+                    float sv[4];
+    #pragma unroll
+                    for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * a.scale_log2;
+                    if (masked) {
+    #pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (4 * lq + i >= n_col - tok0) sv[i] = -INFINITY;
+                    }
+
+                    // ---- raise the reference maximum if some score is far above it (always on the first tile)
+                    float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+                    if (__builtin_amdgcn_ballot_w64(mx > m_run + kBump) != 0) {
+                        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                        const float m_new = fmaxf(m_run, mx);
+                        const float alpha = m_new == m_run ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
+                        l_run *= alpha;
+    #pragma unroll
+                        for (int nb_ = 0; nb_ < NDB; ++nb_)
+    #pragma unroll
+                            for (int i = 0; i < 4; ++i) o[nb_][i] *= alpha;
+                        m_run = m_new;
+                    }
+
+                    // ---- weights, rounded to bf16; their sum uses the rounded values, so out is an exact
+                    //      convex combination of V rows -------------------------------------------------
+                    float p[4];
+    #pragma unroll
+                    for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - m_run);
+                    if (masked) {     // a column that has seen nothing yet has m = -inf: its weights are 0, not exp2(nan)
+    #pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (sv[i] == -INFINITY) p[i] = 0.f;
+                    }
+                    const bf16x4_t pb = __builtin_convertvector(f32x4_t{p[0], p[1], p[2], p[3]}, bf16x4_t);
+    #pragma unroll
+                    for (int i = 0; i < 4; ++i) l_run += static_cast<float>(pb[i]);
+
+                    // ---- O^T[d][head] += V^T P ---------------------------------------------------------
+    #pragma unroll
+                    for (int nb_ = 0; nb_ < NDB; ++nb_)
+                        o[nb_] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt[nb_], __builtin_bit_cast(i16x4_t, pb), o[nb_], 0, 0, 0);
+                }
                 c_stage = c_stage + 1 == kStages ? 0 : c_stage + 1;
                 --ahead;
             }

@@ -37,16 +37,16 @@ hipError_t launch_valu(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int D, bool DEEP>
+template <int D, bool DEEP, bool KV8>
 hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
 {
     const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
     switch (G) {
-    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1, DEEP>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2, DEEP>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4, DEEP>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8, DEEP>), grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16, DEEP>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1, DEEP, KV8>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2, DEEP, KV8>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4, DEEP, KV8>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8, DEEP, KV8>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16, DEEP, KV8>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -105,12 +105,45 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, i
                                     workspace_bytes, out, lse, B, 1, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream);
 }
 
+namespace {
+int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
+                  const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                  int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
+                  int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
+                  bool kv8, float k_scale, float v_scale, void *hip_stream);
+}  // namespace
+
 extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_t n_rows,
                                         const fairkv_item *items,
                                         const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
                                         int32_t n_slots, int32_t n_parts, void *workspace, size_t workspace_bytes,
                                         void *out, float *lse, int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv,
                                         int32_t D, int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream)
+{
+    return decode_common(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, in_dtype, out_dtype, scale, false, 1.f, 1.f,
+                         hip_stream);
+}
+
+extern "C" int fairkv_decode_attn_kv8(const void *q, const void *k8, const void *v8, int64_t n_rows, float k_scale,
+                                      float v_scale, const fairkv_item *items, const fairkv_item *items_host,
+                                      int32_t n_items, const int32_t *slot_ptr, int32_t n_slots, int32_t n_parts,
+                                      void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
+                                      int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t out_dtype, float scale,
+                                      void *hip_stream)
+{
+    if (!(k_scale == k_scale) || !(v_scale == v_scale) || std::isinf(k_scale) || std::isinf(v_scale)) return FAIRKV_EINVAL;
+    return decode_common(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, true, k_scale,
+                         v_scale, hip_stream);
+}
+
+namespace {
+int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
+                  const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                  int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
+                  int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
+                  bool kv8, float k_scale, float v_scale, void *hip_stream)
 {
     if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
     if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1 || n_rows < 0) return FAIRKV_EINVAL;
@@ -142,6 +175,7 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
     const int64_t cols = static_cast<int64_t>(G) * q_len;
     if (cols != 1 && cols != 2 && cols != 4 && cols != 8 && cols != 16) return FAIRKV_EUNSUPPORTED;
     if (q_len > 1 && (in_dtype != FAIRKV_BF16 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
+    if (kv8 && (D != 128 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
     if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items) || !aligned16(out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
@@ -162,9 +196,9 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
         if (slot_ptr[j] == slot_ptr[j + 1]) continue;
         const fairkv_item &it = items_host[slot_ptr[j]];
         const int64_t pair = static_cast<int64_t>(it.b) * Hkv + it.h;
-        if (it.row > static_cast<int64_t>(UINT32_MAX) || pair >= (1 << 24)) continue;   // does not fit: normal start
+        if (it.row > static_cast<int64_t>(UINT32_MAX) || pair >= (1 << 23)) continue;   // does not fit: normal start
         a.first_row[j] = static_cast<uint32_t>(it.row);
-        a.first_np[j] = (static_cast<uint32_t>(pair) << 8) | static_cast<uint32_t>(it.tok_count < kEarlyTok ? it.tok_count : kEarlyTok);
+        a.first_np[j] = (static_cast<uint32_t>(pair) << 9) | static_cast<uint32_t>(it.tok_count < kEarlyTok ? it.tok_count : kEarlyTok);
     }
     a.arrivals = reinterpret_cast<int32_t *>(ws);
     a.group_arrivals = a.arrivals + static_cast<size_t>(B) * Hkv;
@@ -183,20 +217,24 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
     a.n_rows = n_rows;
     a.q_len = q_len;
     a.g_shift = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : 3;
-    a.scale_log2 = scale * kLog2e;
+    a.scale_log2 = scale * kLog2e * k_scale;
+    a.v_scale = v_scale;
 
     hipError_t e;
     if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())
-        e = D == 128 ? (deep ? launch_mfma<128, true>(static_cast<int>(cols), a, n_slots, st)
-                             : launch_mfma<128, false>(static_cast<int>(cols), a, n_slots, st))
-                     : (deep ? launch_mfma<64, true>(static_cast<int>(cols), a, n_slots, st)
-                             : launch_mfma<64, false>(static_cast<int>(cols), a, n_slots, st));
+        e = kv8 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_slots, st)
+                        : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_slots, st))
+            : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), a, n_slots, st)
+                               : launch_mfma<128, false, false>(static_cast<int>(cols), a, n_slots, st))
+                       : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), a, n_slots, st)
+                               : launch_mfma<64, false, false>(static_cast<int>(cols), a, n_slots, st));
     else if (in_dtype == FAIRKV_BF16)
         e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_slots, st);
     else
         e = D == 128 ? launch_valu<FAIRKV_F32, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_F32, 64>(G, a, n_slots, st);
     return e == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
 }
+}  // namespace
 
 // ---- packing and appending ------------------------------------------------------------------------
 namespace {

@@ -9,7 +9,8 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import Plan, fairkv_decode_attn, fairkv_default_params, fairkv_plan, fairkv_workspace_bytes
+from . import (Plan, fairkv_decode_attn, fairkv_decode_attn_kv8, fairkv_default_params, fairkv_plan,
+               fairkv_workspace_bytes)
 
 
 def device_compute_units(device=None) -> int:
@@ -22,11 +23,13 @@ class DecodeLayer:
     """One layer's packed ragged KV cache, its plan and its output buffers on the GPU."""
 
     def __init__(self, q, k, v, off, lens, scale, params=None, out_dtype=None, want_lse=True,
-                 workspace=None):
+                 workspace=None, k_scale=1.0, v_scale=1.0):
         import torch
 
         dev = q.device
         self.q, self.k, self.v = q, k, v
+        self.kv8 = k.dtype in (torch.uint8, torch.float8_e4m3fn)   # a cache of 8-bit floats, one scale per tensor
+        self.k_scale, self.v_scale = float(k_scale), float(v_scale)
         self.q_len = q.shape[1] if q.dim() == 4 else 1     # several new tokens per sequence: q [B,q_len,Hq,D]
         self.B, self.Hq, self.D = q.shape[0], q.shape[-2], q.shape[-1]
         lens_h = np.ascontiguousarray(np.asarray(lens, dtype=np.int32))
@@ -35,7 +38,10 @@ class DecodeLayer:
         self.G = self.Hq // self.Hkv
         self.scale = float(scale)
         if params is None:
-            params = fairkv_default_params(device_compute_units(dev))
+            # 8-bit caches: a step covers 32 tokens and a token costs half the bytes, so the per-item
+            # overhead is worth twice as many tokens
+            extra = {"tile": 32, "min_chunk": 64, "overhead_tokens": 256} if self.kv8 else {}
+            params = fairkv_default_params(device_compute_units(dev), **extra)
         self.plan: Plan = fairkv_plan(lens_h, off_h, self.B, self.Hkv, params)
         self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
         need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G * self.q_len, self.D)
@@ -48,6 +54,11 @@ class DecodeLayer:
         self.lse = torch.empty(tuple(q.shape[:-1]), dtype=torch.float32, device=dev) if want_lse else None
 
     def run(self, stream=None):
+        if self.kv8:
+            fairkv_decode_attn_kv8(self.q, self.k, self.v, self.k_scale, self.v_scale, self.items_d, self.plan.items,
+                                   self.plan.slot_ptr, self.plan.n_parts, self.workspace, self.out, self.lse,
+                                   self.scale, self.Hkv, stream)
+            return self.out, self.lse
         fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.items, self.plan.slot_ptr, self.plan.n_parts,
                            self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
         return self.out, self.lse

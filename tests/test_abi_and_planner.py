@@ -26,7 +26,7 @@ def _built():
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "fairkv.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(fairkv_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(fairkv_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(F.EXPORTS)
     L = F.lib()
     for name in declared:

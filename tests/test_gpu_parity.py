@@ -357,3 +357,107 @@ def test_pairs_cut_into_very_many_pieces_are_merged_in_two_levels():
     w, off, q, k, v = make_case(1, 6, 3, 64, "bf16", lens, seed=5)
     err, layer = check(w, q, k, v, off, lens, policy=2, n_slots=64, min_chunk=32, oversub=4, calls=2)
     assert layer.plan.items["n_chunks"].max() > 8
+
+
+# ---- a cache stored as 8-bit floats ---------------------------------------------------------------
+def _kv8_case(B, Hkv, G, lens, seed, q_len=1, gap_rows=2):
+    w = W.Workload("case", B, Hkv * G, Hkv, 128, "bf16", 1, 1e-2, "")
+    off, total = W.packed_offsets(lens, gap_rows=gap_rows)
+    k_scale, v_scale = 0.0173, 0.0291                 # not powers of two: a scale applied to the wrong side shows
+    k8, v8 = W.make_kv8(w, total + 8, k_scale, v_scale, seed=seed)
+    g = torch.Generator().manual_seed(seed + 77)
+    shape = (B, q_len, Hkv * G, 128) if q_len > 1 else (B, Hkv * G, 128)
+    q = torch.randn(shape, generator=g).to(torch.bfloat16)
+    return w, off, q, k8, v8, k_scale, v_scale
+
+
+def _kv8_check(w, off, lens, q, k8, v8, k_scale, v_scale, out_dtype=None, **params):
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    ro, rl = OA.attention_kv8(W.to_numpy_bits(q), k8.numpy(), v8.numpy(), off, lens, w.scale, k_scale, v_scale)
+    p = F.fairkv_default_params(256, **params)
+    layer = DecodeLayer(q.cuda(), k8.cuda(), v8.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype,
+                        k_scale=k_scale, v_scale=v_scale)
+    for _ in range(2):
+        layer.out.fill_(float("nan"))
+        layer.lse.fill_(float("nan"))
+        layer.workspace[F.fairkv_workspace_counter_bytes(lens.size):].fill_(0xFF)
+        layer.run()
+        torch.cuda.synchronize()
+    out = layer.out.float().cpu().numpy().astype(np.float64)
+    lse = layer.lse.cpu().numpy().astype(np.float64)
+    assert out.shape == ro.shape and np.isfinite(out).all()
+    err = np.abs(out - ro).max()
+    assert err <= w.tol, f"max abs err {err:.3e}"
+    empty = np.isneginf(rl)
+    assert (np.isneginf(lse) == empty).all() and (out[empty] == 0).all()
+    if (~empty).any():
+        assert np.abs(lse[~empty] - rl[~empty]).max() <= w.tol
+    return layer
+
+
+@pytest.mark.parametrize("G", [8, 4, 2, 1])
+def test_kv8_shapes_with_ragged_tails_and_chunks(G):
+    rng = np.random.default_rng(800 + G)
+    B, Hkv = 3, 2
+    lens = rng.integers(1, 900, size=(B, Hkv)).astype(np.int32)
+    lens[0, 0] = 1                    # a single row
+    lens[0, 1] = 31                   # one row short of a 32-token step
+    lens[1, 0] = 0                    # an empty head
+    lens[1, 1] = 32 * 4 * 3           # whole steps for every wave
+    lens[2, 0] = 33
+    case = _kv8_case(B, Hkv, G, lens, seed=G)
+    w, off, q, k8, v8, ks, vs = case
+    for policy, n_slots, mc in ((3, 16, 32), (0, 16, 32), (3, 5, 16), (3, 300, 16), (2, 40, 64)):
+        _kv8_check(w, off, lens, q, k8, v8, ks, vs, policy=policy, n_slots=n_slots, min_chunk=mc, oversub=2)
+
+
+def test_kv8_length_one_returns_the_scaled_value_row():
+    lens = np.ones((2, 2), np.int32)
+    w, off, q, k8, v8, ks, vs = _kv8_case(2, 2, 4, lens, seed=5)
+    layer = _kv8_check(w, off, lens, q, k8, v8, ks, vs)
+    out = layer.out.cpu().numpy()
+    want = v8.view(torch.float8_e4m3fn).float().numpy() * np.float32(vs)
+    for b in range(2):
+        for h in range(2):
+            for g in range(4):
+                assert np.array_equal(out[b, h * 4 + g], want[off[b, h]])     # one weight of exactly 1, one product
+
+
+@pytest.mark.parametrize("G,QL", [(8, 2), (4, 4), (1, 16)])
+def test_kv8_several_new_tokens(G, QL):
+    rng = np.random.default_rng(900 + G)
+    B, Hkv = 2, 2
+    lens = rng.integers(QL, 600, size=(B, Hkv)).astype(np.int32)
+    lens[0, 0] = max(QL - 1, 1)
+    lens[1, 1] = 64 * 4 + 1
+    w, off, q, k8, v8, ks, vs = _kv8_case(B, Hkv, G, lens, seed=G + QL, q_len=QL)
+    for policy, n_slots, mc in ((3, 16, 32), (3, 300, 16), (0, 4, 32)):
+        _kv8_check(w, off, lens, q, k8, v8, ks, vs, policy=policy, n_slots=n_slots, min_chunk=mc, oversub=2)
+
+
+def test_kv8_full_size_headline_workload():
+    w = W.WORKLOADS["llama70b"]
+    lens = W.lens("llama70b")
+    off, total = W.packed_offsets(lens)
+    ks, vs = 0.02, 0.03
+    k8, v8 = W.make_kv8(w, total, ks, vs, seed=3)
+    q, _, _ = W.make_qkv(w, 1, seed=3)
+    _kv8_check(w, off, lens, q, k8, v8, ks, vs, out_dtype=torch.bfloat16)
+
+
+def test_kv8_argument_checks():
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    lens = np.full((1, 1), 40, np.int32)
+    off, total = W.packed_offsets(lens)
+    q = torch.randn((1, 8, 64)).to(torch.bfloat16)                # head_dim 64 is not built for 8-bit caches
+    k8 = torch.zeros((total, 64), dtype=torch.uint8)
+    with pytest.raises(F.FairKVError) as e:
+        DecodeLayer(q.cuda(), k8.cuda(), k8.cuda(), off, lens, 0.125).run()
+    assert e.value.code == F.FAIRKV_EUNSUPPORTED
+    q = torch.randn((1, 8, 128)).to(torch.bfloat16)
+    k8 = torch.zeros((total, 128), dtype=torch.uint8)
+    with pytest.raises(F.FairKVError) as e:
+        DecodeLayer(q.cuda(), k8.cuda(), k8.cuda(), off, lens, 0.125, k_scale=float("inf")).run()
+    assert e.value.code == F.FAIRKV_EINVAL

@@ -172,6 +172,22 @@ def make_qkv(w: Workload, n_rows: int, seed: int = 0, layer: int = 0, device: st
     return q, k, v
 
 
+def make_kv8(w: Workload, n_rows: int, k_scale: float, v_scale: float, seed: int = 0, layer: int = 0,
+             device: str = "cpu"):
+    """The K and V of make_qkv stored as 8-bit floats (E4M3, finite-only encoding): uint8 [n_rows,D] each.
+
+    A stored byte stands for value / scale, clamped to the format's largest finite magnitude (448) and
+    rounded by torch's own conversion; this only manufactures input bytes, what they mean is for the
+    oracle and the kernel to decode, each on its own.
+    """
+    import torch
+
+    _, k, v = make_qkv(w, n_rows, seed=seed, layer=layer, device=device)
+    k8 = (k.float() / k_scale).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+    v8 = (v.float() / v_scale).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+    return k8, v8
+
+
 def to_numpy_bits(t):
     """torch tensor -> numpy array the oracle accepts (bf16 as uint16 bit patterns)."""
     import torch
