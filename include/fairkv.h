@@ -48,7 +48,8 @@ typedef enum {
     FAIRKV_EHIP = -5          /* a HIP call failed; the HIP error is left for hipGetLastError */
 } fairkv_status;
 
-enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1 };
+enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1,
+       FAIRKV_E4M3 = 2 /* one byte per element: fairkv_pack and fairkv_append only (they move bytes) */ };
 enum { FAIRKV_MAX_SLOTS = 320 };   /* most slots a plan handed to fairkv_decode_attn may have */
 
 /* How the work list is built; the four mirror the paper's ablation (Section 5.2.1).

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfairkv.so")
 
 FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, FAIRKV_EHIP = 0, -1, -2, -3, -4, -5
-FAIRKV_BF16, FAIRKV_F32 = 0, 1
+FAIRKV_BF16, FAIRKV_F32, FAIRKV_E4M3 = 0, 1, 2
 FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
@@ -322,7 +322,8 @@ def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_
 
 def _dtype_code(t):
     import torch
-    return {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32}[t.dtype]
+    return {torch.bfloat16: FAIRKV_BF16, torch.float32: FAIRKV_F32, torch.uint8: FAIRKV_E4M3,
+            torch.float8_e4m3fn: FAIRKV_E4M3}[t.dtype]
 
 
 def _check_dev(**tensors):

@@ -240,8 +240,8 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
 namespace {
 int row_bytes_of(int32_t D, int32_t dtype)
 {
-    if (dtype != FAIRKV_BF16 && dtype != FAIRKV_F32) return 0;
-    const int64_t rb = static_cast<int64_t>(D) * (dtype == FAIRKV_BF16 ? 2 : 4);
+    if (dtype != FAIRKV_BF16 && dtype != FAIRKV_F32 && dtype != FAIRKV_E4M3) return 0;
+    const int64_t rb = static_cast<int64_t>(D) * (dtype == FAIRKV_E4M3 ? 1 : dtype == FAIRKV_BF16 ? 2 : 4);
     return (rb == 128 || rb == 256 || rb == 512) ? static_cast<int>(rb) : 0;
 }
 }  // namespace

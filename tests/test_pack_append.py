@@ -61,7 +61,7 @@ def test_pack_and_append_reject_bad_arguments_without_a_gpu():
     assert L.fairkv_pack(one, one, 1, 1, 1, 128, 0, one, one, one, one, one, 0, one, one, 1, null, null) == F.FAIRKV_EINVAL
     assert L.fairkv_pack(one, one, 1, 1, 1, 96, 0, one, one, one, one, one, 1, one, one, 1, null, null) == F.FAIRKV_EUNSUPPORTED
     assert L.fairkv_pack(ctypes.c_void_p(8), one, 1, 1, 1, 128, 0, one, one, one, one, one, 1, one, one, 1, null, null) == F.FAIRKV_EINVAL
-    assert L.fairkv_append(one, one, 1, 1, 128, 2, one, one, one, one, one, 1, null, null) == F.FAIRKV_EUNSUPPORTED
+    assert L.fairkv_append(one, one, 1, 1, 128, 3, one, one, one, one, one, 1, null, null) == F.FAIRKV_EUNSUPPORTED
     assert L.fairkv_append(one, null, 1, 1, 128, 0, one, one, one, one, one, 1, null, null) == F.FAIRKV_EINVAL
     assert L.fairkv_append(one, one, 0, 1, 128, 0, one, one, one, one, one, 1, null, null) == F.FAIRKV_EINVAL
 
@@ -69,6 +69,8 @@ def test_pack_and_append_reject_bad_arguments_without_a_gpu():
 # ---- GPU -------------------------------------------------------------------------------------
 def _bits(t):
     import torch
+    if t.dtype == torch.uint8:
+        return t.cpu().numpy()
     return t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else \
         t.view(torch.int32).cpu().numpy().view(np.uint32)
 
@@ -77,8 +79,12 @@ def _case(B, Hkv, T, D, dtype, lens, gap, seed, n_slots, policy=3):
     import torch
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     g = torch.Generator().manual_seed(seed)
-    kd = torch.randn((B, Hkv, T, D), generator=g).to(tdt)
-    vd = torch.randn((B, Hkv, T, D), generator=g).to(tdt)
+    if dtype == "u8":                                       # a cache of 8-bit floats: any bytes will do here
+        kd = torch.randint(0, 256, (B, Hkv, T, D), generator=g, dtype=torch.uint8)
+        vd = torch.randint(0, 256, (B, Hkv, T, D), generator=g, dtype=torch.uint8)
+    else:
+        kd = torch.randn((B, Hkv, T, D), generator=g).to(tdt)
+        vd = torch.randn((B, Hkv, T, D), generator=g).to(tdt)
     keep_ptr, keep_t = W.keep_lists(lens, T, seed=seed, recent=8)
     off, total = W.packed_offsets(lens, gap_rows=gap)
     p = F.fairkv_default_params(n_slots, policy=policy, overhead_tokens=16, min_chunk=32)
@@ -87,7 +93,7 @@ def _case(B, Hkv, T, D, dtype, lens, gap, seed, n_slots, policy=3):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("u8", 128)])
 def test_pack_matches_the_oracle_byte_for_byte(dtype, D):
     import torch
     rng = np.random.default_rng(D)
@@ -97,8 +103,8 @@ def test_pack_matches_the_oracle_byte_for_byte(dtype, D):
     for n_slots, policy, gap in ((64, 3, 3), (7, 0, 0), (300, 2, 5)):
         kd, vd, keep_ptr, keep_t, off, total, plan = _case(B, Hkv, T, D, dtype, lens, gap, seed=D + gap, n_slots=n_slots,
                                                             policy=policy)
-        k = torch.full((total + 4, D), 7.0, dtype=kd.dtype, device="cuda")
-        v = torch.full((total + 4, D), 9.0, dtype=kd.dtype, device="cuda")
+        k = torch.full((total + 4, D), 7, dtype=kd.dtype, device="cuda")
+        v = torch.full((total + 4, D), 9, dtype=kd.dtype, device="cuda")
         rk, rv = _bits(k).copy(), _bits(v).copy()
         PK.pack(_bits(kd), _bits(vd), keep_ptr, keep_t, off.reshape(-1), rk, rv)
         bad = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -185,3 +191,44 @@ def test_append_then_attend_over_the_grown_cache(dtype, D):
     ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k.cpu()), W.to_numpy_bits(v.cpu()), off, l_ref.reshape(B, Hkv),
                           w.scale)
     assert np.abs(out.float().cpu().numpy() - ro).max() <= w.tol
+
+
+@pytest.mark.gpu
+def test_cache_of_8bit_floats_packed_grown_and_attended():
+    """The whole chain on E4M3 bytes: gather the kept tokens, append one decode step's rows, attend."""
+    import torch
+    from oracle import attention as OA
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    rng = np.random.default_rng(11)
+    B, Hkv, G, T, D = 3, 2, 4, 400, 128
+    ks, vs = 0.021, 0.017
+    lens = rng.integers(1, 350, size=(B, Hkv)).astype(np.int32)
+    cap = (lens + 1).astype(np.int32)
+    off, total = W.packed_offsets(cap)
+    w = W.Workload("case", B, Hkv * G, Hkv, D, "bf16", 1, 1e-2, "")
+    dense = W.Workload("dense", 1, 1, 1, D, "bf16", 1, 1e-2, "")
+    kd, vd = (t.view(B, Hkv, T, D) for t in W.make_kv8(dense, B * Hkv * T, ks, vs, seed=4))
+    kn, vn = (t.view(B, Hkv, D) for t in W.make_kv8(dense, B * Hkv, ks, vs, seed=5))
+    keep_ptr, keep_t = W.keep_lists(lens, T, seed=3, recent=8)
+    plan = F.fairkv_plan(lens, off, B, Hkv, F.fairkv_default_params(16, min_chunk=32))
+    k = torch.zeros((total, D), dtype=torch.uint8, device="cuda")
+    v = torch.zeros((total, D), dtype=torch.uint8, device="cuda")
+    rk, rv = np.zeros((total, D), np.uint8), np.zeros((total, D), np.uint8)
+    l_ref = lens.reshape(-1).copy()
+    PK.pack(kd.numpy(), vd.numpy(), keep_ptr, keep_t, off.reshape(-1), rk, rv)
+    PK.append(rk, rv, kn.numpy(), vn.numpy(), off.reshape(-1), l_ref, cap.reshape(-1))
+    off_d = torch.from_numpy(off.reshape(-1)).cuda()
+    l_dev = torch.from_numpy(lens.reshape(-1).copy()).cuda()
+    F.fairkv_pack(kd.cuda(), vd.cuda(), torch.from_numpy(keep_ptr).cuda(), torch.from_numpy(keep_t).cuda(), off_d,
+                  torch.from_numpy(plan.items.view(np.uint8).copy()).cuda(), torch.from_numpy(plan.slot_ptr).cuda(), k, v)
+    F.fairkv_append(kn.cuda(), vn.cuda(), off_d, l_dev, torch.from_numpy(cap.reshape(-1)).cuda(), k, v)
+    torch.cuda.synchronize()
+    assert (k.cpu().numpy() == rk).all() and (v.cpu().numpy() == rv).all() and l_dev.cpu().numpy().tolist() == l_ref.tolist()
+    g = torch.Generator().manual_seed(9)
+    q = torch.randn((B, Hkv * G, D), generator=g).to(torch.bfloat16)
+    grown = l_ref.reshape(B, Hkv)
+    layer = DecodeLayer(q.cuda(), k, v, off, grown, w.scale, k_scale=ks, v_scale=vs)
+    out, lse = layer.run()
+    torch.cuda.synchronize()
+    ro, rl = OA.attention_kv8(W.to_numpy_bits(q), rk, rv, off, grown, w.scale, ks, vs)
+    assert np.abs(out.float().cpu().numpy() - ro).max() <= w.tol and np.abs(lse.cpu().numpy() - rl).max() <= w.tol
