@@ -559,7 +559,7 @@ def main():
         "plan_layer0": {"max_slot_load": loads_max, "min_slot_load": loads_min, "efficiency_E": round(eff0, 4)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None if kv8 else measured_traffic(a.workload),
-                     "kernel": f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}{', KV8' if kv8 else ''}>",
+                     "kernel": f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}, DEEP, {'true' if kv8 else 'false'}>",
                      "bytes_per_launch": round(moved / a.steps), "us_per_launch": round(1e3 * ms_step, 3)},
         "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
                          "(Llama-3.3-70B, Section 5.2.2); other hardware, not this metric",
