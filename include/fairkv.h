@@ -276,11 +276,11 @@ int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_
  * k8, v8   device [n_rows][D] bytes: E4M3 in the finite-only encoding (1 sign, 4 exponent bits with
  *          bias 7, 3 mantissa bits; no infinities; S.1111.111 is NaN and must not occur).  A stored
  *          byte x stands for the value x * k_scale (x * v_scale): one scale per tensor.
- * q        device bf16 [B][q_len][Hq][D], D = 128; out, lse, items, slot_ptr, workspace, n_rows,
+ * q        device bf16 [B][q_len][Hq][D], D 64 or 128; out, lse, items, slot_ptr, workspace, n_rows,
  *          q_len as in fairkv_decode_attn_multi (q_len = 1: fairkv_decode_attn).
  * The bytes are widened to bf16 exactly and the products run as in the bf16 path, k_scale folded
  * into the softmax scale and v_scale into the final normalisation.
- * Returns FAIRKV_EUNSUPPORTED for D != 128, FAIRKV_EINVAL for a scale that is not finite. */
+ * Returns FAIRKV_EINVAL for a scale that is not finite. */
 int fairkv_decode_attn_kv8(const void *q, const void *k8, const void *v8, int64_t n_rows,
                            float k_scale, float v_scale,
                            const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,

@@ -281,7 +281,7 @@ def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_
     """fairkv_decode_attn over a cache stored as 8-bit floats (E4M3, finite-only "fn" encoding).
 
     k8, v8 [rows,D]: torch.float8_e4m3fn or uint8 holding the same bytes; a stored byte stands for
-    value * k_scale (v_scale).  q [B,Hq,D] or [B,q_len,Hq,D] bfloat16, D = 128.  Everything else as in
+    value * k_scale (v_scale).  q [B,Hq,D] or [B,q_len,Hq,D] bfloat16.  Everything else as in
     fairkv_decode_attn.
     """
     import torch

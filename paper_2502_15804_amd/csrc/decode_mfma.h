@@ -134,7 +134,6 @@ template <int D, int G, bool DEEP, bool KV8>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
-    static_assert(!KV8 || D == 128, "8-bit caches: head_dim 128 only");
     static_assert(G >= 1 && G <= 16, "query heads of a group fit the N dimension");
     constexpr int TOK = KV8 ? 2 * kTok : kTok;          // tokens per stage and per step
     constexpr int kEarly = kStages < 3 ? kStages : 3;   // tiles per wave the early start may request

@@ -175,7 +175,7 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
     const int64_t cols = static_cast<int64_t>(G) * q_len;
     if (cols != 1 && cols != 2 && cols != 4 && cols != 8 && cols != 16) return FAIRKV_EUNSUPPORTED;
     if (q_len > 1 && (in_dtype != FAIRKV_BF16 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
-    if (kv8 && (D != 128 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
+    if (kv8 && bf16_on_valu()) return FAIRKV_EUNSUPPORTED;
     if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items) || !aligned16(out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
@@ -222,8 +222,10 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
 
     hipError_t e;
     if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())
-        e = kv8 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_slots, st)
-                        : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_slots, st))
+        e = kv8 ? (D == 128 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_slots, st)
+                                    : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_slots, st))
+                            : (deep ? launch_mfma<64, true, true>(static_cast<int>(cols), a, n_slots, st)
+                                    : launch_mfma<64, false, true>(static_cast<int>(cols), a, n_slots, st)))
             : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), a, n_slots, st)
                                : launch_mfma<128, false, false>(static_cast<int>(cols), a, n_slots, st))
                        : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), a, n_slots, st)

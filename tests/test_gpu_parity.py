@@ -360,13 +360,13 @@ def test_pairs_cut_into_very_many_pieces_are_merged_in_two_levels():
 
 
 # ---- a cache stored as 8-bit floats ---------------------------------------------------------------
-def _kv8_case(B, Hkv, G, lens, seed, q_len=1, gap_rows=2):
-    w = W.Workload("case", B, Hkv * G, Hkv, 128, "bf16", 1, 1e-2, "")
+def _kv8_case(B, Hkv, G, lens, seed, q_len=1, gap_rows=2, D=128):
+    w = W.Workload("case", B, Hkv * G, Hkv, D, "bf16", 1, 1e-2, "")
     off, total = W.packed_offsets(lens, gap_rows=gap_rows)
     k_scale, v_scale = 0.0173, 0.0291                 # not powers of two: a scale applied to the wrong side shows
     k8, v8 = W.make_kv8(w, total + 8, k_scale, v_scale, seed=seed)
     g = torch.Generator().manual_seed(seed + 77)
-    shape = (B, q_len, Hkv * G, 128) if q_len > 1 else (B, Hkv * G, 128)
+    shape = (B, q_len, Hkv * G, D) if q_len > 1 else (B, Hkv * G, D)
     q = torch.randn(shape, generator=g).to(torch.bfloat16)
     return w, off, q, k8, v8, k_scale, v_scale
 
@@ -396,9 +396,9 @@ def _kv8_check(w, off, lens, q, k8, v8, k_scale, v_scale, out_dtype=None, **para
     return layer
 
 
-@pytest.mark.parametrize("G", [8, 4, 2, 1])
-def test_kv8_shapes_with_ragged_tails_and_chunks(G):
-    rng = np.random.default_rng(800 + G)
+@pytest.mark.parametrize("G,D", [(8, 128), (4, 128), (2, 128), (1, 128), (8, 64), (2, 64), (1, 64)])
+def test_kv8_shapes_with_ragged_tails_and_chunks(G, D):
+    rng = np.random.default_rng(800 + G + D)
     B, Hkv = 3, 2
     lens = rng.integers(1, 900, size=(B, Hkv)).astype(np.int32)
     lens[0, 0] = 1                    # a single row
@@ -406,7 +406,7 @@ def test_kv8_shapes_with_ragged_tails_and_chunks(G):
     lens[1, 0] = 0                    # an empty head
     lens[1, 1] = 32 * 4 * 3           # whole steps for every wave
     lens[2, 0] = 33
-    case = _kv8_case(B, Hkv, G, lens, seed=G)
+    case = _kv8_case(B, Hkv, G, lens, seed=G, D=D)
     w, off, q, k8, v8, ks, vs = case
     for policy, n_slots, mc in ((3, 16, 32), (0, 16, 32), (3, 5, 16), (3, 300, 16), (2, 40, 64)):
         _kv8_check(w, off, lens, q, k8, v8, ks, vs, policy=policy, n_slots=n_slots, min_chunk=mc, oversub=2)
@@ -424,14 +424,14 @@ def test_kv8_length_one_returns_the_scaled_value_row():
                 assert np.array_equal(out[b, h * 4 + g], want[off[b, h]])     # one weight of exactly 1, one product
 
 
-@pytest.mark.parametrize("G,QL", [(8, 2), (4, 4), (1, 16)])
-def test_kv8_several_new_tokens(G, QL):
+@pytest.mark.parametrize("G,QL,D", [(8, 2, 128), (4, 4, 128), (1, 16, 128), (4, 2, 64)])
+def test_kv8_several_new_tokens(G, QL, D):
     rng = np.random.default_rng(900 + G)
     B, Hkv = 2, 2
     lens = rng.integers(QL, 600, size=(B, Hkv)).astype(np.int32)
     lens[0, 0] = max(QL - 1, 1)
     lens[1, 1] = 64 * 4 + 1
-    w, off, q, k8, v8, ks, vs = _kv8_case(B, Hkv, G, lens, seed=G + QL, q_len=QL)
+    w, off, q, k8, v8, ks, vs = _kv8_case(B, Hkv, G, lens, seed=G + QL, q_len=QL, D=D)
     for policy, n_slots, mc in ((3, 16, 32), (3, 300, 16), (0, 4, 32)):
         _kv8_check(w, off, lens, q, k8, v8, ks, vs, policy=policy, n_slots=n_slots, min_chunk=mc, oversub=2)
 
@@ -451,8 +451,8 @@ def test_kv8_argument_checks():
     from paper_2502_15804_amd.runtime import DecodeLayer
     lens = np.full((1, 1), 40, np.int32)
     off, total = W.packed_offsets(lens)
-    q = torch.randn((1, 8, 64)).to(torch.bfloat16)                # head_dim 64 is not built for 8-bit caches
-    k8 = torch.zeros((total, 64), dtype=torch.uint8)
+    q = torch.randn((1, 8, 32)).to(torch.bfloat16)                # head_dim 32 is not built
+    k8 = torch.zeros((total, 32), dtype=torch.uint8)
     with pytest.raises(F.FairKVError) as e:
         DecodeLayer(q.cuda(), k8.cuda(), k8.cuda(), off, lens, 0.125).run()
     assert e.value.code == F.FAIRKV_EUNSUPPORTED
