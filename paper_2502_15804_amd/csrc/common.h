@@ -190,65 +190,66 @@ enum { kRoleNone = 0, kRoleFinal = 1, kRoleGroup = 2 };
 template <int D, int G, bool DEEP>
 __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
 {
-    // A thread owns four consecutive coordinates of one column.  The first batch of loads of ALL
-    // pending merges is issued before any is used: one memory round trip, not one per pair.
-    constexpr int D4 = D / 4;
+    // A thread owns four consecutive coordinates of one column (of two columns, when there are 16 of them).
+    // The first batch of loads of ALL pending merges and of all the thread's coordinates is issued before
+    // any is used: one memory round trip, not one per pair or per coordinate.
+    constexpr int D4 = D / 4, NC4 = G * D4;
     constexpr int kPend = pend_slots(D, G);
-    for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
-        const int g = idx / D4, d = (idx % D4) * 4;
-        float2 ml[kPend][kMergeBatch], o01[kPend][kMergeBatch], o23[kPend][kMergeBatch];
+    constexpr int IT = (NC4 + kThreads - 1) / kThreads;            // coordinates per thread
+    constexpr int MB = IT > 1 ? kMergeBatch / 2 : kMergeBatch;     // 6 IT kPend MB registers hold the batches
+    float2 ml[IT][kPend][MB], o01[IT][kPend][MB], o23[IT][kPend][MB];
+    auto fetch_batch = [&](int it, int p, int c0) {
+        const int idx = threadIdx.x + it * kThreads, g = idx / D4, d = (idx % D4) * 4;
+        const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
 #pragma unroll
-        for (int p = 0; p < kPend; ++p) {
-            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
-            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
-#pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j) {
-                ml[p][j] = make_float2(-INFINITY, 0.f);        // past the end: weight 0 below, and no load
-                o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
-                if (j < nc) {
-                    const size_t pg = static_cast<size_t>(p0 + st * j) * G + g;
-                    ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
-                    o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
-                    o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
-                }
+        for (int j = 0; j < MB; ++j) {
+            ml[it][p][j] = make_float2(-INFINITY, 0.f);        // past the end: weight 0 below, and no load
+            o01[it][p][j] = o23[it][p][j] = make_float2(0.f, 0.f);
+            if (c0 + j < nc) {
+                const size_t pg = static_cast<size_t>(p0 + st * (c0 + j)) * G + g;
+                ml[it][p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                o01[it][p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                o23[it][p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
             }
         }
+    };
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        if (threadIdx.x + it * kThreads >= NC4) continue;
 #pragma unroll
         for (int p = 0; p < kPend; ++p) {
             if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
-            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p], pair = pend.pair[p];
-            float m_star = -INFINITY, l_star = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
-                if (c0 > 0) {   // more than kMergeBatch partials: fetch the next batch
+            fetch_batch(it, p, 0);
+        }
+    }
 #pragma unroll
-                    for (int j = 0; j < kMergeBatch; ++j) {
-                        ml[p][j] = make_float2(-INFINITY, 0.f);
-                        o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
-                        if (c0 + j < nc) {
-                            const size_t pg = static_cast<size_t>(p0 + st * (c0 + j)) * G + g;
-                            ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
-                            o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
-                            o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
-                        }
-                    }
-                }
+    for (int it = 0; it < IT; ++it) {
+        const int idx = threadIdx.x + it * kThreads, g = idx / D4, d = (idx % D4) * 4;
+        if (idx >= NC4) continue;
+#pragma unroll
+        for (int p = 0; p < kPend; ++p) {
+            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
+            const int nc = pend.src_count[p], p0 = pend.src_first[p], pair = pend.pair[p];
+            float m_star = -INFINITY, l_star = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c0 = 0; c0 < nc; c0 += MB) {
+                if (c0 > 0) fetch_batch(it, p, c0);     // more than MB partials: the next batch
                 float m_new = m_star;
 #pragma unroll
-                for (int j = 0; j < kMergeBatch; ++j)
-                    if (c0 + j < nc) m_new = fmaxf(m_new, ml[p][j].x);
+                for (int j = 0; j < MB; ++j)
+                    if (c0 + j < nc) m_new = fmaxf(m_new, ml[it][p][j].x);
                 const float keep = m_star == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_star - m_new);
                 l_star *= keep;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e] *= keep;
 #pragma unroll
-                for (int j = 0; j < kMergeBatch; ++j) {
-                    const bool live = c0 + j < nc && ml[p][j].x != -INFINITY;
-                    const float f = live ? __builtin_amdgcn_exp2f(ml[p][j].x - m_new) : 0.f;
-                    l_star = fmaf(ml[p][j].y, f, l_star);
-                    acc[0] = fmaf(o01[p][j].x, f, acc[0]);
-                    acc[1] = fmaf(o01[p][j].y, f, acc[1]);
-                    acc[2] = fmaf(o23[p][j].x, f, acc[2]);
-                    acc[3] = fmaf(o23[p][j].y, f, acc[3]);
+                for (int j = 0; j < MB; ++j) {
+                    const bool live = c0 + j < nc && ml[it][p][j].x != -INFINITY;
+                    const float f = live ? __builtin_amdgcn_exp2f(ml[it][p][j].x - m_new) : 0.f;
+                    l_star = fmaf(ml[it][p][j].y, f, l_star);
+                    acc[0] = fmaf(o01[it][p][j].x, f, acc[0]);
+                    acc[1] = fmaf(o01[it][p][j].y, f, acc[1]);
+                    acc[2] = fmaf(o23[it][p][j].x, f, acc[2]);
+                    acc[3] = fmaf(o23[it][p][j].y, f, acc[3]);
                 }
                 m_star = m_new;
             }
