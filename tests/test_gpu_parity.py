@@ -461,3 +461,67 @@ def test_kv8_argument_checks():
     with pytest.raises(F.FairKVError) as e:
         DecodeLayer(q.cuda(), k8.cuda(), k8.cuda(), off, lens, 0.125, k_scale=float("inf")).run()
     assert e.value.code == F.FAIRKV_EINVAL
+
+
+# ---- many small random configurations --------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_configurations(seed):
+    """Shapes, budgets, policies, slot counts, storage and the number of new tokens drawn at random (valid
+    inputs only): the element-by-element bar holds for every draw."""
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    rng = np.random.default_rng(4000 + seed)
+    D = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    QL = int(rng.choice([q for q in (1, 1, 2, 4, 8, 16) if G * q <= 16]))
+    kv8 = bool(rng.integers(0, 2))
+    B, Hkv = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    kind = int(rng.integers(0, 3))
+    if kind == 0:                                  # mostly short, a few long
+        lens = rng.integers(0, 80, size=(B, Hkv))
+        lens[rng.integers(0, B), rng.integers(0, Hkv)] = int(rng.integers(500, 3000))
+    elif kind == 1:                                # around whole tiles and steps
+        lens = rng.choice([15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257], size=(B, Hkv))
+    else:
+        lens = rng.integers(0, 700, size=(B, Hkv))
+    lens = np.maximum(lens, QL - 1 if rng.integers(0, 2) else 0).astype(np.int32)
+    policy = int(rng.choice([0, 1, 2, 3, 3, 3]))
+    n_slots = int(rng.choice([1, 3, 17, 64, 256, 320]))
+    tile = int(rng.choice([16, 32]))
+    params = dict(policy=policy, n_slots=n_slots, tile=tile, min_chunk=tile * int(rng.integers(1, 5)),
+                  oversub=int(rng.integers(1, 4)), overhead_tokens=int(rng.choice([0, 16, 128, 256])),
+                  max_split=int(rng.choice([2, 8, 256])))
+    w = W.Workload("case", B, Hkv * G, Hkv, D, "bf16", 1, 1e-2, "")
+    off, total = W.packed_offsets(lens, gap_rows=int(rng.integers(0, 4)))
+    g = torch.Generator().manual_seed(seed)
+    shape = (B, QL, Hkv * G, D) if QL > 1 else (B, Hkv * G, D)
+    q = torch.randn(shape, generator=g).to(torch.bfloat16)
+    ks, vs = (0.019, 0.023) if kv8 else (1.0, 1.0)
+    if kv8:
+        k, v = W.make_kv8(w, total + 4, ks, vs, seed=seed)
+        ro, rl = OA.attention_kv8(W.to_numpy_bits(q), k.numpy(), v.numpy(), off, lens, w.scale, ks, vs)
+    else:
+        _, k, v = W.make_qkv(w, total + 4, seed=seed)
+        fn = OA.attention_multi if QL > 1 else OA.attention
+        ro, rl = fn(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=F.fairkv_default_params(256, **params),
+                        k_scale=ks, v_scale=vs)
+    it = layer.plan.items
+    if QL > 1 and ((it["n_chunks"] > 1) & (it["chunk"] == it["n_chunks"] - 1) & (it["tok_count"] < QL - 1)).any():
+        with pytest.raises(F.FairKVError):          # a last chunk shorter than the rows to hide: refused
+            layer.run()
+        return
+    for _ in range(2):
+        layer.out.fill_(float("nan"))
+        layer.lse.fill_(float("nan"))
+        layer.run()
+        torch.cuda.synchronize()
+    out = layer.out.cpu().numpy().astype(np.float64)
+    lse = layer.lse.cpu().numpy().astype(np.float64)
+    what = dict(D=D, G=G, QL=QL, kv8=kv8, B=B, Hkv=Hkv, **params)
+    assert np.isfinite(out).all(), what
+    assert np.abs(out - ro).max() <= w.tol, (what, np.abs(out - ro).max())
+    empty = np.isneginf(rl)
+    assert (np.isneginf(lse) == empty).all() and (out[empty] == 0).all(), what
+    if (~empty).any():
+        assert np.abs(lse[~empty] - rl[~empty]).max() <= w.tol, what
