@@ -188,7 +188,91 @@ constexpr int kDeepFrom = 32;
 enum { kRoleNone = 0, kRoleFinal = 1, kRoleGroup = 2 };
 
 template <int D, int G, bool DEEP>
-__device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
+__device__ __forceinline__ void merge_round_one(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
+{
+    // A thread owns four consecutive coordinates of one column.  The first batch of loads of ALL
+    // pending merges is issued before any is used: one memory round trip, not one per pair.
+    constexpr int D4 = D / 4;
+    constexpr int kPend = pend_slots(D, G);
+    for (int idx = threadIdx.x; idx < G * D4; idx += kThreads) {
+        const int g = idx / D4, d = (idx % D4) * 4;
+        float2 ml[kPend][kMergeBatch], o01[kPend][kMergeBatch], o23[kPend][kMergeBatch];
+#pragma unroll
+        for (int p = 0; p < kPend; ++p) {
+            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
+            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                ml[p][j] = make_float2(-INFINITY, 0.f);        // past the end: weight 0 below, and no load
+                o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
+                if (j < nc) {
+                    const size_t pg = static_cast<size_t>(p0 + st * j) * G + g;
+                    ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                    o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                    o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kPend; ++p) {
+            if (p >= n_pend || pend.role[p] == kRoleNone || pend.src_count[p] < 2) continue;
+            const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p], pair = pend.pair[p];
+            float m_star = -INFINITY, l_star = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c0 = 0; c0 < nc; c0 += kMergeBatch) {
+                if (c0 > 0) {   // more than kMergeBatch partials: fetch the next batch
+#pragma unroll
+                    for (int j = 0; j < kMergeBatch; ++j) {
+                        ml[p][j] = make_float2(-INFINITY, 0.f);
+                        o01[p][j] = o23[p][j] = make_float2(0.f, 0.f);
+                        if (c0 + j < nc) {
+                            const size_t pg = static_cast<size_t>(p0 + st * (c0 + j)) * G + g;
+                            ml[p][j] = fetch_f32x2(a.part_ml + pg * 2);
+                            o01[p][j] = fetch_f32x2(a.part_o + pg * D + d);
+                            o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
+                        }
+                    }
+                }
+                float m_new = m_star;
+#pragma unroll
+                for (int j = 0; j < kMergeBatch; ++j)
+                    if (c0 + j < nc) m_new = fmaxf(m_new, ml[p][j].x);
+                const float keep = m_star == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_star - m_new);
+                l_star *= keep;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] *= keep;
+#pragma unroll
+                for (int j = 0; j < kMergeBatch; ++j) {
+                    const bool live = c0 + j < nc && ml[p][j].x != -INFINITY;
+                    const float f = live ? __builtin_amdgcn_exp2f(ml[p][j].x - m_new) : 0.f;
+                    l_star = fmaf(ml[p][j].y, f, l_star);
+                    acc[0] = fmaf(o01[p][j].x, f, acc[0]);
+                    acc[1] = fmaf(o01[p][j].y, f, acc[1]);
+                    acc[2] = fmaf(o23[p][j].x, f, acc[2]);
+                    acc[3] = fmaf(o23[p][j].y, f, acc[3]);
+                }
+                m_star = m_new;
+            }
+            if (DEEP && pend.role[p] == kRoleGroup) {  // the group's partial, in the slot of its first piece
+                const size_t pg = static_cast<size_t>(p0) * G + g;
+                publish_f32x4(a.part_o + pg * D + d, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                if (d == 0) {
+                    publish_f32(a.part_ml + pg * 2 + 0, m_star);
+                    publish_f32(a.part_ml + pg * 2 + 1, l_star);
+                }
+                continue;
+            }
+            const int b = pair / a.Hkv, h = pair % a.Hkv;
+            const size_t orow = out_row(a, b, h, g);
+            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
+            store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
+            if (d == 0 && a.lse)
+                a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
+        }
+    }
+}
+
+template <int D, int G, bool DEEP>
+__device__ __forceinline__ void merge_round_many(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
 {
     // A thread owns four consecutive coordinates of one column (of two columns, when there are 16 of them).
     // The first batch of loads of ALL pending merges and of all the thread's coordinates is issued before
@@ -270,6 +354,18 @@ __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D,
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
         }
     }
+}
+
+// Up to 256 float4 coordinates (G * D <= 1024) a thread owns at most one: the plain loop, whose code is the
+// shorter (0.2 us per launch on the headline workload: this code runs cold, on the tail).  With more, all of
+// a thread's coordinates are fetched together.
+template <int D, int G, bool DEEP>
+__device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
+{
+    if constexpr (G * D / 4 <= kThreads)
+        merge_round_one<D, G, DEEP>(a, pend, n_pend);
+    else
+        merge_round_many<D, G, DEEP>(a, pend, n_pend);
 }
 
 // DEEP: the plan has a pair in kDeepFrom pieces or more.  Without it the group code is not even compiled
