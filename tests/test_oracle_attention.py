@@ -375,3 +375,23 @@ def test_kv8_attention_is_attention_over_the_dequantised_cache():
     o2, l2 = OA.attention_kv8(qbits, k8, v8, off, lens, 0.15, 1.0, 0.5)
     live = lens.repeat(G, axis=1) > 0
     assert np.allclose(o2[live], 2 * out[live], rtol=1e-12, atol=0) and np.allclose(l2[live], lse[live], rtol=1e-12, atol=1e-12)
+
+
+def test_e4m3_decoder_against_the_hand_decoded_fixture():
+    """tests/golden/e4m3_codes.txt: codes decoded by hand from the format's definition."""
+    import math
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "e4m3_codes.txt")
+    n = 0
+    for line in open(path):
+        if not line.strip() or line.startswith("#"):
+            continue
+        code, value = [f.strip() for f in line.split("|")]
+        got = float(OA.decode_e4m3fn(np.array([int(code, 16)], dtype=np.uint8))[0])
+        want = float(value)
+        if math.isnan(want):
+            assert math.isnan(got), line
+        else:
+            assert got == want and math.copysign(1.0, got) == math.copysign(1.0, want), line
+        n += 1
+    assert n == 16

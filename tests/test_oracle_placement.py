@@ -181,3 +181,22 @@ def test_static_head_allocation_baseline():
     assert PL.static_head_allocation([5, 1, 2, 2, 7, 0, 1, 1], 4) == [6, 4, 7, 2]
     with pytest.raises(ValueError):
         PL.static_head_allocation([1, 2, 3], 2)
+
+
+def test_worked_cases_of_the_fixture_file():
+    """tests/golden/placement_worked_cases.txt: cases checked by hand against Algorithms 1 and 2."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "placement_worked_cases.txt")
+    n = 0
+    for line in open(path):
+        if not line.strip() or line.startswith("#"):
+            continue
+        W, tp, m, cap, copies, gpus, loads, den = [[int(x) for x in f.split()] for f in line.split("|")]
+        c, g, ld = PL.search_exact(W, tp[0], m[0], cap[0])
+        assert list(c) == copies and list(g) == gpus and list(ld) == loads, line
+        shares, ld2, s = PL.place(W, 4, PL.PlaceParams(tp=tp[0], max_extra=m[0], max_copies=cap[0], mode=PL.MODE_EXACT))
+        assert ld2 == loads and s.den == den[0] and [sh.gpu for sh in shares] == gpus, line
+        assert s.delta_num == max(loads) - min(loads)                                   # eq. 4's quantity
+        assert abs(s.efficiency - sum(loads) / (tp[0] * max(loads))) < 1e-12            # eq. 5
+        n += 1
+    assert n == 6
