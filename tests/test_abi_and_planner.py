@@ -202,3 +202,36 @@ def test_decode_attn_validates_before_any_launch():
     assert call(odt=2) == F.FAIRKV_EUNSUPPORTED
     assert call(ws_bytes=16) == F.FAIRKV_EWORKSPACE
     assert call(ws=None) == F.FAIRKV_EWORKSPACE
+
+
+def test_decode_attn_kv8_and_multi_validate_before_any_launch():
+    """The entry points for 8-bit caches and for several new tokens reject bad calls on the host as well."""
+    L = F.lib()
+    fake = ctypes.c_void_p(0x1000)
+    sp = np.array([0, 1], np.int32)
+    it = np.zeros(1, F.ITEM_DTYPE)
+    it["tok_count"], it["n_chunks"] = 5, 1
+
+    def kv8(q=fake, ks=0.02, vs=0.03, D=128, q_len=1, Hq=8, odt=1, ws_bytes=1 << 30, n_rows=5):
+        return L.fairkv_decode_attn_kv8(q, fake, fake, n_rows, ks, vs, fake, it.ctypes.data, 1, sp.ctypes.data, 1, 1, fake,
+                                        ws_bytes, fake, None, 1, q_len, Hq, 1, D, odt, 0.1, None)
+
+    assert kv8(ks=float("nan")) == F.FAIRKV_EINVAL
+    assert kv8(vs=float("inf")) == F.FAIRKV_EINVAL
+    assert kv8(q=None) == F.FAIRKV_EINVAL
+    assert kv8(n_rows=4) == F.FAIRKV_EINVAL
+    assert kv8(D=32) == F.FAIRKV_EUNSUPPORTED
+    assert kv8(odt=2) == F.FAIRKV_EUNSUPPORTED
+    assert kv8(q_len=3) == F.FAIRKV_EUNSUPPORTED                   # 8 heads x 3 tokens: not a supported column count
+    assert kv8(q_len=0) == F.FAIRKV_EINVAL
+    assert kv8(ws_bytes=16) == F.FAIRKV_EWORKSPACE
+
+    def multi(q_len=2, idt=0, Hq=8, tok=5, n_chunks=1, chunk=0, part=0, n_parts=1):
+        it2 = it.copy()
+        it2["tok_count"], it2["n_chunks"], it2["chunk"], it2["part"] = tok, n_chunks, chunk, part
+        return L.fairkv_decode_attn_multi(fake, fake, fake, 5, fake, it2.ctypes.data, 1, sp.ctypes.data, 1, n_parts, fake,
+                                          1 << 30, fake, None, 1, q_len, Hq, 1, 128, idt, 1, 0.1, None)
+
+    assert multi(idt=1) == F.FAIRKV_EUNSUPPORTED                   # fp32 inputs take the single-token path only
+    assert multi(q_len=4) == F.FAIRKV_EUNSUPPORTED                 # 32 columns
+    assert multi(q_len=4, Hq=4, tok=2, n_chunks=2, chunk=1, part=1, n_parts=2) == F.FAIRKV_EINVAL   # last chunk shorter than q_len - 1
