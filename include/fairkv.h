@@ -290,6 +290,18 @@ int fairkv_decode_attn_kv8(const void *q, const void *k8, const void *v8, int64_
                            int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D,
                            int32_t out_dtype, float scale, void *hip_stream);
 
+/* The same with a scale per KV head: k_scale, v_scale host [Hkv], Hkv <= 8 (else FAIRKV_EUNSUPPORTED); a
+ * stored byte of head h stands for byte * k_scale[h] (v_scale[h]).  The scales travel in the kernel
+ * arguments; nothing else differs from fairkv_decode_attn_kv8. */
+int fairkv_decode_attn_kv8_per_head(const void *q, const void *k8, const void *v8, int64_t n_rows,
+                                    const float *k_scale, const float *v_scale,
+                                    const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                                    const int32_t *slot_ptr, int32_t n_slots,
+                                    int32_t n_parts, void *workspace, size_t workspace_bytes,
+                                    void *out, float *lse,
+                                    int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                    int32_t out_dtype, float scale, void *hip_stream);
+
 /* ---- building and growing the packed cache (the step before the path) ---------------------------
  *
  * fairkv_pack gathers the tokens a per-head compressor kept (Section 2: which entries a method

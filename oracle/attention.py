@@ -145,14 +145,27 @@ def decode_e4m3fn(codes):
 
 def attention_kv8(q, k8, v8, off, lens, scale, k_scale, v_scale, n_threads=0):
     """The same attention over a cache stored as 8-bit floats (E4M3) with one scale factor for K and
-    one for V: K = k_scale * decode(k8), V = v_scale * decode(v8), everything else in fp64.
+    one for V (or one per KV head each, as sequences): K = k_scale * decode(k8), V = v_scale * decode(v8),
+    everything else in fp64.
     q: bf16 bit patterns (uint16), [B,Hq,D] or [B,q_len,Hq,D]; k8, v8: uint8 [rows,D]."""
     q = np.ascontiguousarray(q)
     if q.dtype != np.uint16:
         raise TypeError("q must be bf16 bit patterns (uint16)")
     q64 = (q.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
-    k64 = decode_e4m3fn(k8) * float(k_scale)
-    v64 = decode_e4m3fn(v8) * float(v_scale)
+    k64 = decode_e4m3fn(k8)
+    v64 = decode_e4m3fn(v8)
+    if np.ndim(k_scale) == 0 and np.ndim(v_scale) == 0:
+        k64 *= float(k_scale)
+        v64 *= float(v_scale)
+    else:                       # a scale per KV head: the rows of pair (b, h) carry the scales of head h
+        lens_a, off_a = np.asarray(lens), np.asarray(off)
+        ks = np.broadcast_to(np.asarray(k_scale, dtype=np.float64), (lens_a.shape[1],))
+        vs = np.broadcast_to(np.asarray(v_scale, dtype=np.float64), (lens_a.shape[1],))
+        for b in range(lens_a.shape[0]):
+            for h in range(lens_a.shape[1]):
+                r0, n = int(off_a[b, h]), int(lens_a[b, h])
+                k64[r0:r0 + n] *= ks[h]
+                v64[r0:r0 + n] *= vs[h]
     if q.ndim == 4:
         return attention_multi(q64, k64, v64, off, lens, scale, n_threads=n_threads)
     return attention(q64, k64, v64, off, lens, scale, n_threads=n_threads)

@@ -24,7 +24,7 @@ FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_workspace_counter_bytes",
            "fairkv_decode_attn",
-           "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8",
+           "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8", "fairkv_decode_attn_kv8_per_head",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
@@ -113,6 +113,10 @@ def lib() -> ctypes.CDLL:
         L.fairkv_decode_attn_kv8.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_float, ctypes.c_float, vp, vp, i32, vp,
                                              i32, i32, vp, ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32,
                                              ctypes.c_float, vp]
+        L.fairkv_decode_attn_kv8_per_head.restype = ctypes.c_int
+        L.fairkv_decode_attn_kv8_per_head.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, vp, vp, i32, vp,
+                                                      i32, i32, vp, ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                      ctypes.c_float, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -281,7 +285,8 @@ def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_
     """fairkv_decode_attn over a cache stored as 8-bit floats (E4M3, finite-only "fn" encoding).
 
     k8, v8 [rows,D]: torch.float8_e4m3fn or uint8 holding the same bytes; a stored byte stands for
-    value * k_scale (v_scale).  q [B,Hq,D] or [B,q_len,Hq,D] bfloat16.  Everything else as in
+    value * k_scale (v_scale).  k_scale and v_scale are two numbers, or two sequences of Hkv numbers (a scale
+    per KV head: fairkv_decode_attn_kv8_per_head).  q [B,Hq,D] or [B,q_len,Hq,D] bfloat16.  Everything else as in
     fairkv_decode_attn.
     """
     import torch
@@ -311,13 +316,20 @@ def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_
         raise TypeError("items_host must be the plan's contiguous item array, as many records as `items`")
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
-    rc = lib().fairkv_decode_attn_kv8(
-        _ptr(q), _ptr(k8), _ptr(v8), k8.shape[0], float(k_scale), float(v_scale), _ptr(items), items_host.ctypes.data,
-        item_bytes // 32, slot_ptr.ctypes.data, slot_ptr.size - 1, int(n_parts), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, dt[out.dtype],
-        float(scale), ctypes.c_void_p(stream.cuda_stream))
+    tail = (_ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data, slot_ptr.size - 1, int(n_parts),
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D,
+            dt[out.dtype], float(scale), ctypes.c_void_p(stream.cuda_stream))
+    if np.ndim(k_scale) or np.ndim(v_scale):
+        ks = np.ascontiguousarray(np.broadcast_to(np.asarray(k_scale, dtype=np.float32), (Hkv,)))
+        vs = np.ascontiguousarray(np.broadcast_to(np.asarray(v_scale, dtype=np.float32), (Hkv,)))
+        rc = lib().fairkv_decode_attn_kv8_per_head(_ptr(q), _ptr(k8), _ptr(v8), k8.shape[0], ks.ctypes.data, vs.ctypes.data,
+                                                   *tail)
+        name = "fairkv_decode_attn_kv8_per_head"
+    else:
+        rc = lib().fairkv_decode_attn_kv8(_ptr(q), _ptr(k8), _ptr(v8), k8.shape[0], float(k_scale), float(v_scale), *tail)
+        name = "fairkv_decode_attn_kv8"
     if rc != FAIRKV_OK:
-        raise FairKVError(rc, "fairkv_decode_attn_kv8")
+        raise FairKVError(rc, name)
 
 
 def _dtype_code(t):

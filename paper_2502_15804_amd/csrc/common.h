@@ -83,6 +83,8 @@ __device__ __forceinline__ float fetch_f32(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+constexpr int kScaleHeads = 8;            // KV heads that may carry scales of their own (8-bit caches)
+
 struct DecodeArgs {
     const void *q, *k, *v;
     const fairkv_item *items;   // grouped by slot
@@ -100,6 +102,8 @@ struct DecodeArgs {
     float scale_log2;           // scale * log2(e) (times the K scale of an 8-bit cache): scores are kept in log2
                                 // units so exp is one v_exp_f32
     float v_scale;              // 1, or the V scale of an 8-bit cache: multiplies out
+    float k_head[kScaleHeads];  // 8-bit caches with a scale per KV head: further factors on scale_log2 and v_scale,
+    float v_head[kScaleHeads];  // indexed h % kScaleHeads (all 1 otherwise; read by the 8-bit kernels only)
     // What a workgroup needs before it has read anything from memory, riding in the kernel arguments:
     int32_t slot_ptr[FAIRKV_MAX_SLOTS + 1];   // slot j runs items[slot_ptr[j] .. slot_ptr[j+1])
     uint32_t first_row[FAIRKV_MAX_SLOTS];     // first K/V row of slot j's first item ...
@@ -155,6 +159,7 @@ struct PendingParts {
     float ml[kPend][G * 2];
     int32_t pair[kPend], part[kPend], first_part[kPend], n_chunks[kPend];
     int32_t role[kPend], src_first[kPend], src_stride[kPend], src_count[kPend];   // what this workgroup merges, if anything
+    float v_mul[kPend];      // what multiplies the pair's output (1, or the V scale of an 8-bit cache)
 };
 
 // s_waitcnt vmcnt(0), once as an instruction the compiler accounts for (simm16 of gfx9: vmcnt 0,
@@ -263,7 +268,7 @@ __device__ __forceinline__ void merge_round_one(const DecodeArgs &a, PendingPart
             }
             const int b = pair / a.Hkv, h = pair % a.Hkv;
             const size_t orow = out_row(a, b, h, g);
-            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
+            const float inv = l_star > 0.f ? pend.v_mul[p] / l_star : 0.f;
             store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             if (d == 0 && a.lse)
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
@@ -348,7 +353,7 @@ __device__ __forceinline__ void merge_round_many(const DecodeArgs &a, PendingPar
             }
             const int b = pair / a.Hkv, h = pair % a.Hkv;
             const size_t orow = out_row(a, b, h, g);
-            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
+            const float inv = l_star > 0.f ? pend.v_mul[p] / l_star : 0.f;
             store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             if (d == 0 && a.lse)
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
@@ -444,7 +449,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
 // partial (m*, l*, o*) in `pend`.  Ends with a barrier, so st_o/st_ml may be reused at once.
 template <int D, int G, bool DEEP>
 __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
-                                              const float *st_ml, PendingParts<D, G> &pend, int &n_pend)
+                                              const float *st_ml, PendingParts<D, G> &pend, int &n_pend, float v_mul)
 {
     const int b = it.b, h = it.h;
     const bool whole_pair = it.n_chunks == 1;
@@ -476,7 +481,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
         }
         if (whole_pair) {
             const size_t orow = out_row(a, b, h, g);
-            const float inv = l_star > 0.f ? a.v_scale / l_star : 0.f;
+            const float inv = l_star > 0.f ? v_mul / l_star : 0.f;
             store_out4(a.out, a.out_dtype, orow * D + d, make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
             if (d == 0 && a.lse)
                 a.lse[orow] = l_star > 0.f ? (m_star + __builtin_amdgcn_logf(l_star)) * kLn2 : -INFINITY;
@@ -494,6 +499,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
             pend.part[n_pend] = it.part;
             pend.first_part[n_pend] = it.part - it.chunk;   // the partials of a pair are consecutive
             pend.n_chunks[n_pend] = it.n_chunks;
+            pend.v_mul[n_pend] = v_mul;
         }
         ++n_pend;
         if (n_pend == pend_slots(D, G)) {

@@ -367,6 +367,10 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             it.part = __builtin_amdgcn_readfirstlane(table[ci].part);
             const int n = __builtin_amdgcn_readfirstlane(table[ci].n);
             const int my_tiles = tiles_of(n);
+            // scores to log2 units, and what multiplies the output: the same for every pair unless an 8-bit cache has
+            // a scale per KV head
+            const float s_mul = KV8 ? a.scale_log2 * a.k_head[it.h % kScaleHeads] : a.scale_log2;
+            const float v_mul = KV8 ? a.v_scale * a.v_head[it.h % kScaleHeads] : a.v_scale;
             // Several new tokens per sequence: their K/V rows are the last q_len rows of the pair, and
             // new token j does not see the rows of the new tokens after it.  Only the pair's last
             // chunk holds such rows; n_col = tokens of this item the lane's column may see.
@@ -419,7 +423,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     const bool masked = n - hidden_max - tok0 < TOK;     // some column does not see the whole step
                     float sv[8];
 #pragma unroll
-                    for (int r = 0; r < 8; ++r) sv[r] = sacc[r >> 2][r & 3] * a.scale_log2;
+                    for (int r = 0; r < 8; ++r) sv[r] = sacc[r >> 2][r & 3] * s_mul;
                     if (masked) {
 #pragma unroll
                         for (int r = 0; r < 8; ++r)
@@ -480,7 +484,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     const bool masked = n - hidden_max - tok0 < TOK;    // some column does not see the whole tile
                     float sv[4];
     #pragma unroll
-                    for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * a.scale_log2;
+                    for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * s_mul;
                     if (masked) {
     #pragma unroll
                         for (int i = 0; i < 4; ++i)
@@ -538,7 +542,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     st_ml[(wave * G + l16) * 2 + 1] = l_run;
                 }
             }
-            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G, DEEP>(a, it, st_o, st_ml, pend, n_pend);
+            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G, DEEP>(a, it, st_o, st_ml, pend, n_pend, v_mul);
         }
         wait_vmcnt<0>();   // nothing of this batch may still be landing in the rings
     }

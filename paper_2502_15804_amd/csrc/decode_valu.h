@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kThreads, 2) void fairkv_decode_valu_kernel(DecodeA
             st_ml[(wave * G + g) * 2 + 1] = l_lane[g];
         }
     }
-    item_epilogue<D, G, true>(a, it, st_o, st_ml, pend, n_pend);
+    item_epilogue<D, G, true>(a, it, st_o, st_ml, pend, n_pend, a.v_scale);
     }   // items of the slot
     if (n_pend > 0) flush_pending<D, G, true>(a, pend, n_pend);
 }

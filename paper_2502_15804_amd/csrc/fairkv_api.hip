@@ -110,7 +110,7 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
                   const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
                   int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
                   int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
-                  bool kv8, float k_scale, float v_scale, void *hip_stream);
+                  bool kv8, float k_scale, float v_scale, const float *k_head, const float *v_head, void *hip_stream);
 }  // namespace
 
 extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_t n_rows,
@@ -122,7 +122,7 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
 {
     return decode_common(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
                          workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, in_dtype, out_dtype, scale, false, 1.f, 1.f,
-                         hip_stream);
+                         nullptr, nullptr, hip_stream);
 }
 
 extern "C" int fairkv_decode_attn_kv8(const void *q, const void *k8, const void *v8, int64_t n_rows, float k_scale,
@@ -135,7 +135,24 @@ extern "C" int fairkv_decode_attn_kv8(const void *q, const void *k8, const void 
     if (!(k_scale == k_scale) || !(v_scale == v_scale) || std::isinf(k_scale) || std::isinf(v_scale)) return FAIRKV_EINVAL;
     return decode_common(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
                          workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, true, k_scale,
-                         v_scale, hip_stream);
+                         v_scale, nullptr, nullptr, hip_stream);
+}
+
+extern "C" int fairkv_decode_attn_kv8_per_head(const void *q, const void *k8, const void *v8, int64_t n_rows,
+                                               const float *k_scale, const float *v_scale, const fairkv_item *items,
+                                               const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
+                                               int32_t n_slots, int32_t n_parts, void *workspace, size_t workspace_bytes,
+                                               void *out, float *lse, int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv,
+                                               int32_t D, int32_t out_dtype, float scale, void *hip_stream)
+{
+    if (!k_scale || !v_scale || Hkv < 1) return FAIRKV_EINVAL;
+    if (Hkv > kScaleHeads) return FAIRKV_EUNSUPPORTED;
+    for (int32_t h = 0; h < Hkv; ++h)
+        if (!(k_scale[h] == k_scale[h]) || !(v_scale[h] == v_scale[h]) || std::isinf(k_scale[h]) || std::isinf(v_scale[h]))
+            return FAIRKV_EINVAL;
+    return decode_common(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, true, 1.f, 1.f,
+                         k_scale, v_scale, hip_stream);
 }
 
 namespace {
@@ -143,7 +160,7 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
                   const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
                   int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
                   int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
-                  bool kv8, float k_scale, float v_scale, void *hip_stream)
+                  bool kv8, float k_scale, float v_scale, const float *k_head, const float *v_head, void *hip_stream)
 {
     if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
     if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1 || n_rows < 0) return FAIRKV_EINVAL;
@@ -219,6 +236,10 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
     a.g_shift = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : 3;
     a.scale_log2 = scale * kLog2e * k_scale;
     a.v_scale = v_scale;
+    for (int h = 0; h < kScaleHeads; ++h) {     // a scale per KV head (at most kScaleHeads of them), else all 1
+        a.k_head[h] = k_head ? k_head[h % Hkv] : 1.f;
+        a.v_head[h] = v_head ? v_head[h % Hkv] : 1.f;
+    }
 
     hipError_t e;
     if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())

@@ -29,7 +29,8 @@ class DecodeLayer:
         dev = q.device
         self.q, self.k, self.v = q, k, v
         self.kv8 = k.dtype in (torch.uint8, torch.float8_e4m3fn)   # a cache of 8-bit floats, one scale per tensor
-        self.k_scale, self.v_scale = float(k_scale), float(v_scale)
+        self.k_scale = k_scale if np.ndim(k_scale) else float(k_scale)     # a number, or one per KV head
+        self.v_scale = v_scale if np.ndim(v_scale) else float(v_scale)
         self.q_len = q.shape[1] if q.dim() == 4 else 1     # several new tokens per sequence: q [B,q_len,Hq,D]
         self.B, self.Hq, self.D = q.shape[0], q.shape[-2], q.shape[-1]
         lens_h = np.ascontiguousarray(np.asarray(lens, dtype=np.int32))

@@ -525,3 +525,30 @@ def test_random_small_configurations(seed):
     assert (np.isneginf(lse) == empty).all() and (out[empty] == 0).all(), what
     if (~empty).any():
         assert np.abs(lse[~empty] - rl[~empty]).max() <= w.tol, what
+
+
+def test_kv8_with_a_scale_per_kv_head():
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    rng = np.random.default_rng(77)
+    B, Hkv, G = 3, 4, 2
+    lens = rng.integers(0, 500, size=(B, Hkv)).astype(np.int32)
+    w, off, q, k8, v8, ks, vs = _kv8_case(B, Hkv, G, lens, seed=21)
+    ks_h = [ks, ks * 1.7, ks * 0.6, ks * 1.1]            # the same bytes, read with a scale of its own per head
+    vs_h = [vs * 0.8, vs, vs * 2.5, vs * 1.3]
+    ro, rl = OA.attention_kv8(W.to_numpy_bits(q), k8.numpy(), v8.numpy(), off, lens, w.scale, ks_h, vs_h)
+    for n_slots in (16, 256):
+        layer = DecodeLayer(q.cuda(), k8.cuda(), v8.cuda(), off, lens, w.scale, k_scale=ks_h, v_scale=vs_h,
+                            params=F.fairkv_default_params(256, n_slots=n_slots, min_chunk=32))
+        layer.out.fill_(float("nan"))
+        layer.run()
+        torch.cuda.synchronize()
+        out, lse = layer.out.cpu().numpy().astype(np.float64), layer.lse.cpu().numpy().astype(np.float64)
+        assert np.isfinite(out).all() and np.abs(out - ro).max() <= w.tol
+        empty = np.isneginf(rl)
+        assert (np.isneginf(lse) == empty).all() and np.abs(lse[~empty] - rl[~empty]).max() <= w.tol
+    k9 = torch.zeros((8, 128), dtype=torch.uint8).cuda()
+    with pytest.raises(F.FairKVError) as e:              # more KV heads than scales fit in the kernel arguments
+        DecodeLayer(torch.zeros((1, 9, 128), dtype=torch.bfloat16).cuda(), k9, k9, np.zeros((1, 9), np.int64),
+                    np.zeros((1, 9), np.int32), 0.1, k_scale=[1.0] * 9, v_scale=[1.0] * 9).run()
+    assert e.value.code == F.FAIRKV_EUNSUPPORTED

@@ -395,3 +395,32 @@ def test_e4m3_decoder_against_the_hand_decoded_fixture():
             assert got == want and math.copysign(1.0, got) == math.copysign(1.0, want), line
         n += 1
     assert n == 16
+
+
+def test_kv8_scales_per_head_reduce_to_the_plain_oracle_on_scaled_rows():
+    """A scale per KV head is the per-tensor oracle applied to K and V whose rows were scaled head by head: equal
+    scales give the per-tensor result, and doubling one head's V scale doubles exactly that head's outputs."""
+    rng = np.random.default_rng(3)
+    B, Hkv, G, D = 2, 3, 2, 16
+    lens = rng.integers(1, 30, size=(B, Hkv)).astype(np.int32)
+    off, total = W.packed_offsets(lens, gap_rows=1)
+    k8 = rng.integers(0, 0x7e, size=(total, D)).astype(np.uint8) | (rng.integers(0, 2, size=(total, D)).astype(np.uint8) << 7)
+    v8 = rng.integers(0, 0x7e, size=(total, D)).astype(np.uint8) | (rng.integers(0, 2, size=(total, D)).astype(np.uint8) << 7)
+    import torch
+    q = W.to_numpy_bits(torch.randn((B, Hkv * G, D), generator=torch.Generator().manual_seed(1)).to(torch.bfloat16))
+    o1, l1 = OA.attention_kv8(q, k8, v8, off, lens, 0.3, 0.01, 0.02)
+    o2, l2 = OA.attention_kv8(q, k8, v8, off, lens, 0.3, [0.01] * Hkv, [0.02] * Hkv)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    o3, l3 = OA.attention_kv8(q, k8, v8, off, lens, 0.3, [0.01] * Hkv, [0.02, 0.04, 0.02])
+    assert np.array_equal(l3, l1)
+    assert np.allclose(o3[:, 2:4], 2 * o1[:, 2:4], rtol=1e-14, atol=0) and np.array_equal(o3[:, :2], o1[:, :2])
+    # a K scale per head is a softmax scale per head: against the definition written out for one output
+    ks = [0.01, 0.03, 0.02]
+    o4, l4 = OA.attention_kv8(q, k8, v8, off, lens, 0.3, ks, 0.02)
+    b, h, g = 1, 1, 1
+    r0, n = int(off[b, h]), int(lens[b, h])
+    qv = (q[b, h * G + g].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    s = 0.3 * ks[h] * OA.decode_e4m3fn(k8[r0:r0 + n]) @ qv
+    w_ = np.exp(s - s.max())
+    ref = (w_ / w_.sum()) @ (0.02 * OA.decode_e4m3fn(v8[r0:r0 + n]))
+    assert np.allclose(o4[b, h * G + g], ref, rtol=1e-12, atol=1e-15) and abs(l4[b, h * G + g] - (s.max() + np.log(w_.sum()))) < 1e-12
