@@ -235,3 +235,27 @@ def test_decode_attn_kv8_and_multi_validate_before_any_launch():
     assert multi(idt=1) == F.FAIRKV_EUNSUPPORTED                   # fp32 inputs take the single-token path only
     assert multi(q_len=4) == F.FAIRKV_EUNSUPPORTED                 # 32 columns
     assert multi(q_len=4, Hq=4, tok=2, n_chunks=2, chunk=1, part=1, n_parts=2) == F.FAIRKV_EINVAL   # last chunk shorter than q_len - 1
+
+
+def test_decode_attn_kv8_per_head_validates_before_any_launch():
+    L = F.lib()
+    fake = ctypes.c_void_p(0x1000)
+    sp = np.array([0, 1], np.int32)
+    it = np.zeros(1, F.ITEM_DTYPE)
+    it["tok_count"], it["n_chunks"] = 5, 1
+
+    def call(ks, vs, Hkv=2, Hq=8, D=128):
+        kp = ks.ctypes.data if ks is not None else None
+        vp = vs.ctypes.data if vs is not None else None
+        return L.fairkv_decode_attn_kv8_per_head(fake, fake, fake, 5, kp, vp, fake, it.ctypes.data, 1, sp.ctypes.data, 1, 1,
+                                                 fake, 16, fake, None, 1, 1, Hq, Hkv, D, 1, 0.1, None)
+
+    one = np.ones(16, np.float32)
+    assert call(None, one) == F.FAIRKV_EINVAL
+    assert call(one, None) == F.FAIRKV_EINVAL
+    assert call(one, one, Hkv=9, Hq=9) == F.FAIRKV_EUNSUPPORTED              # more KV heads than scales fit
+    bad = one.copy(); bad[1] = np.nan
+    assert call(bad, one) == F.FAIRKV_EINVAL
+    bad[1] = np.inf
+    assert call(one, bad) == F.FAIRKV_EINVAL
+    assert call(one, one) == F.FAIRKV_EWORKSPACE                             # everything else valid: the 16-byte workspace is too small
