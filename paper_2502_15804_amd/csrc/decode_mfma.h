@@ -161,6 +161,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     __shared__ __attribute__((aligned(16))) float st_o[kWaves * G * D];
     __shared__ __attribute__((aligned(16))) float st_ml[kWaves * G * 2];
     __shared__ PendingParts<D, G> pend;
+    __shared__ float head_mul[2 * kScaleHeads];      // 8-bit caches: the per-head factors, out of the kernel arguments
     int n_pend = 0;
 
     const int lane = threadIdx.x & 63;
@@ -170,6 +171,17 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
 
     const int i_begin = a.slot_ptr[blockIdx.x], i_end = a.slot_ptr[blockIdx.x + 1];
     if (i_end <= i_begin) return;   // an idle slot
+    if constexpr (KV8) {
+        // Fixed indices: scalar loads that come back with the other kernel arguments.  Indexed by the item's head
+        // they would be a scalar load per item, waited for in front of its first tile.
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int i = 0; i < kScaleHeads; ++i) {
+                head_mul[i] = a.scale_log2 * a.k_head[i];
+                head_mul[kScaleHeads + i] = a.v_scale * a.v_head[i];
+            }
+        }                           // read after the barriers that precede the first item
+    }
     const uint32_t ring_lds =
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FAIRKV_LDS_PTR(lds))) + wave * (kStages * STAGEB);
     const char *ring = lds + wave * (kStages * STAGEB);
@@ -369,8 +381,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             const int my_tiles = tiles_of(n);
             // scores to log2 units, and what multiplies the output: the same for every pair unless an 8-bit cache has
             // a scale per KV head
-            const float s_mul = KV8 ? a.scale_log2 * a.k_head[it.h % kScaleHeads] : a.scale_log2;
-            const float v_mul = KV8 ? a.v_scale * a.v_head[it.h % kScaleHeads] : a.v_scale;
+            const float s_mul = KV8 ? head_mul[it.h % kScaleHeads] : a.scale_log2;
+            const float v_mul = KV8 ? head_mul[kScaleHeads + it.h % kScaleHeads] : a.v_scale;
             // Several new tokens per sequence: their K/V rows are the last q_len rows of the pair, and
             // new token j does not see the rows of the new tokens after it.  Only the pair's last
             // chunk holds such rows; n_col = tokens of this item the lane's column may see.
