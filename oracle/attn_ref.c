@@ -113,7 +113,7 @@ int fairkv_oracle_attn(const void *q, const void *k, const void *v,
     (void)n_threads;
 #endif
     int bad = 0;
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
     for (int i = 0; i < total; ++i) {
         const int flat = sel ? sel[i] : i;
         if (flat < 0 || flat >= B * Hq) {
@@ -171,7 +171,7 @@ int fairkv_oracle_attn_multi(const void *q, const void *k, const void *v,
     (void)n_threads;
 #endif
     int bad = 0;
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
     for (int flat = 0; flat < total; ++flat) {
         const int hq = flat % Hq, i = (flat / Hq) % q_len, b = flat / (Hq * q_len), h = hq / G;
         const int64_t len_bh = len[b * Hkv + h];

@@ -333,6 +333,41 @@ def test_multi_token_queries_are_single_token_queries_over_shorter_caches():
         OA.attention_multi(q[:, 0], k, v, off, lens, 0.4)
 
 
+def test_multi_token_queries_reduce_to_library_sdpa_with_an_explicit_mask():
+    """Equal lengths L: the q_len new tokens' rows are the last q_len of every head, and new token i may look at
+    key j exactly when j <= L - q_len + i.  That mask is written out here as a boolean matrix, entry by entry,
+    and handed to the library routine; an off-by-one in the oracle's visibility rule shows as a large error."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(33)
+    for B, Hkv, G, D, L, QL in ((2, 2, 3, 8, 19, 4), (1, 1, 1, 4, 5, 5), (2, 3, 2, 16, 40, 2), (1, 2, 4, 8, 3, 6)):
+        lens = np.full((B, Hkv), L, dtype=np.int32)
+        off, total = W.packed_offsets(lens)
+        q = rng.standard_normal((B, QL, Hkv * G, D))
+        k = rng.standard_normal((total, D))
+        v = rng.standard_normal((total, D))
+        scale = 0.37
+        out, lse = OA.attention_multi(q, k, v, off, lens, scale)
+        mask = torch.zeros((QL, L), dtype=torch.bool)
+        for i in range(QL):
+            for j in range(L):
+                mask[i, j] = j <= L - QL + i              # key j is not one of the new tokens after token i
+        kt = torch.from_numpy(k).reshape(B, Hkv, L, D).repeat_interleave(G, dim=1)
+        vt = torch.from_numpy(v).reshape(B, Hkv, L, D).repeat_interleave(G, dim=1)
+        qt = torch.from_numpy(q).permute(0, 2, 1, 3)      # [B, Hq, QL, D]
+        ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
+        ref = ref.permute(0, 2, 1, 3).numpy()
+        seen = mask.any(dim=1).numpy()                    # a new token that sees no key at all: out 0, lse -inf
+        for i in range(QL):
+            if seen[i]:
+                assert np.abs(out[:, i] - ref[:, i]).max() < 1e-10
+                s = torch.einsum("bhd,bhjd->bhj", qt[:, :, i], kt) * scale
+                want = torch.logsumexp(s.masked_fill(~mask[i], float("-inf")), dim=-1).numpy()
+                assert np.abs(lse[:, i] - want).max() < 1e-10
+            else:
+                assert (out[:, i] == 0).all() and np.isneginf(lse[:, i]).all()
+        assert not seen.all() or QL <= L
+
+
 # ---- a cache stored as 8-bit floats ------------------------------------------------------------
 def test_e4m3_decoding_against_an_independent_converter_and_known_values():
     torch = pytest.importorskip("torch")
