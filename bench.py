@@ -55,6 +55,12 @@ def parse():
     ap.add_argument("--pack", action="store_true",
                     help="instead of the benchmark: time fairkv_pack (dense cache -> packed ragged cache) on the "
                          "llama70b budgets")
+    ap.add_argument("--bf16-kernel", choices=("mfma", "valu"), default="mfma",
+                    help="valu: the bf16 workload through the vector-ALU kernel (FAIRKV_BF16_VALU) instead of the "
+                         "matrix-core kernel: the A/B measurement behind the choice of the matrix cores")
+    ap.add_argument("--phases", action="store_true",
+                    help="instead of the benchmark: one traced launch per layer (fairkv_decode_attn_trace) after a "
+                         "warm rotation; prints where the time of a launch goes, per phase, from the GPU's wall clock")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -71,7 +77,7 @@ class Rotation:
 
     K_SCALE, V_SCALE = 0.02, 0.03      # per-tensor scales of the 8-bit variant (N(0,1) data: well inside +-448)
 
-    def __init__(self, name, n_layers, seed, policy, overrides, q_len=1, kv8=False):
+    def __init__(self, name, n_layers, seed, policy, overrides, q_len=1, kv8=False, bf16_on_valu=False):
         import numpy as np
         import torch
         import workloads as W
@@ -102,7 +108,8 @@ class Rotation:
             if kv8:
                 k, v = W.make_kv8(self.w, total, self.K_SCALE, self.V_SCALE, seed=seed, layer=li, device="cuda")
             self.layers.append(DecodeLayer(q, k, v, off, lens, self.w.scale, params=self.params,
-                                           workspace=self.workspace, k_scale=self.K_SCALE, v_scale=self.V_SCALE))
+                                           workspace=self.workspace, k_scale=self.K_SCALE, v_scale=self.V_SCALE,
+                                           bf16_on_valu=bf16_on_valu))
             self.lens.append(lens)
             self.offs.append(off)
             self.bytes.append(W.algorithmic_bytes(self.w, lens) + (q_len - 1) * self.w.B * self.w.Hq * self.w.D *
@@ -116,57 +123,68 @@ class Rotation:
         for i in range(first, first + count):
             self.layers[i % n].run()
 
-    def capture(self):
+    def capture(self, count):
+        """A HIP graph of `count` launches: layers 0 .. count-1 of the rotation."""
         import torch
         g = torch.cuda.CUDAGraph()
         s = torch.cuda.Stream()
         s.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(s):
-            self.run_eager(0, len(self.layers))       # load code objects before capturing
+            self.run_eager(0, count)                   # load code objects before capturing
         torch.cuda.current_stream().wait_stream(s)
         torch.cuda.synchronize()
         with torch.cuda.graph(g):
-            self.run_eager(0, len(self.layers))
+            self.run_eager(0, count)
         return g
 
 
 def timed(rot, steps, warmup, use_graph):
-    """Returns (seconds by host clock, seconds by HIP events, bytes moved) for exactly `steps` steps."""
+    """Returns (seconds by host clock, seconds by HIP events, bytes moved) for exactly `steps` steps.
+
+    With use_graph the timed region consists of graph replays only, whatever `steps` is: whole rotations are
+    replays of a graph of one rotation, and a remainder (or a run shorter than one rotation) is a graph of
+    exactly that many launches.  Without it every step is enqueued from Python."""
     import torch
     n = len(rot.layers)
-    graph = rot.capture() if use_graph else None
+    full, rest = divmod(steps, n)
+    g_full = rot.capture(n) if (use_graph and full) else None
+    g_rest = rot.capture(rest) if (use_graph and rest) else None
 
-    def go(first, count):
-        full, rest = (count // n, count % n) if (graph is not None and first % n == 0) else (0, count)
-        for _ in range(full):
-            graph.replay()
-        rot.run_eager(first + full * n, rest)
+    def go(count_full, count_rest):
+        if use_graph:
+            for _ in range(count_full):
+                g_full.replay()
+            if count_rest:
+                g_rest.replay()
+        else:
+            rot.run_eager(0, count_full * n + count_rest)
 
-    go(0, warmup)
+    rot.run_eager(0, warmup)                   # the W untimed steps, then one untimed pass of what is timed
+    go(min(full, 1), rest)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    start = (warmup + n - 1) // n * n          # begin the timed steps on a rotation boundary
     t0 = time.perf_counter()
     e0.record()
-    go(start, steps)
+    go(full, rest)
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    moved = sum(rot.bytes[(start + i) % n] for i in range(steps))
+    moved = full * sum(rot.bytes) + sum(rot.bytes[:rest])
     return t1 - t0, e0.elapsed_time(e1) * 1e-3, moved
 
 
 def measured_traffic(workload):
-    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload, or None.
-    (Counters cannot be read from inside the timed run; the summary names the commands that made it.)"""
-    path = os.path.join(ROOT, "profiles", f"fairkv_decode_mfma_kernel_{workload}.txt")
+    """(HBM bytes per launch, file) from the committed rocprofv3 counter summary of this workload, or (None, None).
+    Counters cannot be read from inside the timed run: the figure is the one of the summary under profiles/,
+    which names the commands that made it, and the JSON line says so."""
+    rel = os.path.join("profiles", f"fairkv_decode_mfma_kernel_{workload}.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.strip().startswith("traffic_bytes_per_launch:"):
-                return int(line.split(":")[1])
+                return int(line.split(":")[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def spot_check(rot, n_layers=2, n_samples=48):
@@ -491,6 +509,131 @@ def max_split_sweep(a, n_layers, overrides, gbs_fair):
     return out
 
 
+def uniform_same_bytes(rot, seed):
+    """A layer of about the same bytes as the workload's, perfectly balanced and with nothing to merge: one whole
+    pair per slot, all of one length.  What the same kernel needs when raggedness costs nothing."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_15804_amd.runtime import DecodeLayer
+
+    w = rot.w
+    n_slots = int(rot.params.n_slots)
+    B = max(1, n_slots // w.Hkv)
+    C = int(round(float(np.mean([l.sum() for l in rot.lens])) / (B * w.Hkv) / 16.0)) * 16
+    wu = W.Workload("uniform", B, w.Hq, w.Hkv, w.D, w.dtype, 1, w.tol, "")
+    lens = np.full((B, w.Hkv), C, np.int32)
+    off, total = W.packed_offsets(lens)
+    nbytes = W.algorithmic_bytes(wu, lens)
+    layers = []
+    for i in range(max(2, min(32, int(2.0e9 // nbytes)))):
+        q, k, v = W.make_qkv(wu, total, seed=seed, layer=i, device="cuda")
+        layers.append(DecodeLayer(q, k, v, off, lens, wu.scale, params=rot.params, want_lse=True))
+    us = graph_time_us(layers, nbytes)
+    items = layers[0].plan.n_items
+    del layers
+    torch.cuda.empty_cache()
+    return {"us_per_layer": round(us, 2), "GBs": round(nbytes / us / 1e3, 1), "B": B, "tokens_per_pair": C,
+            "bytes_per_launch": nbytes, "items": items,
+            "what": "same kernel, same plan parameters, one whole pair of equal length per slot: balanced, nothing to merge"}
+
+
+def other_workloads(a, overrides):
+    """The other full-size workloads through the same path and the same timing (graph replays over their own
+    rotation of distinct layers): microseconds per layer, GB/s and fraction of the HBM peak."""
+    import torch
+    import workloads as W
+    out = {}
+    for name in ("mistral24b", "faircopy", "stress"):
+        if name == a.workload:
+            continue
+        n = W.WORKLOADS[name].n_layers
+        r = Rotation(name, n, a.seed, a.policy, overrides)
+        steps = max(4 * n, 128) // n * n
+        _, ev, moved = timed(r, steps, n, not a.no_graph)
+        gbs = moved / ev / 1e9
+        err = spot_check(r, n_layers=1, n_samples=32)
+        out[name] = {"us_per_layer": round(1e6 * ev / steps, 2), "GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                     "bytes_per_launch": round(moved / steps), "layers_rotated": n, "rotation_GB": round(sum(r.bytes) / 1e9, 3),
+                     "steps": steps, "items_layer0": r.layers[0].plan.n_items, "spot_check_max_abs_err": round(err, 6)}
+        if not err <= W.WORKLOADS[name].tol:
+            print(f"bench: {name}: outputs of the timed launches are off by {err}", file=sys.stderr)
+            sys.exit(1)
+        del r
+        torch.cuda.empty_cache()
+    return out
+
+
+def phases(a, overrides):
+    """Where the time of one launch goes: every layer of a warm rotation is launched once through
+    fairkv_decode_attn_trace (the same kernel with wall-clock stamps), preceded by the untraced launch of the
+    layer before it so that the GPU is in the state of a running rotation."""
+    import numpy as np
+    import torch
+    import paper_2502_15804_amd as F
+
+    w_name = a.workload
+    rot = Rotation(w_name, a.layers or min(16, __import__("workloads").WORKLOADS[w_name].n_layers), a.seed, a.policy, overrides)
+    n_slots = int(rot.params.n_slots)
+    S = F.FAIRKV_TRACE_STAMPS
+    for _ in range(3):
+        rot.run_eager(0, len(rot.layers))
+    torch.cuda.synchronize()
+    names = ["start", "item list ready", "first tile landed", "first item streamed (wave 0)", "first item finished",
+             "last item streamed (wave 0)", "hand-over begins", "partials' stores issued", "counted in", "merged",
+             "hand-over ends", "end"]
+    per_layer = []
+    rows = {k: [] for k in ("has_handover", "merges", "n_items", "tokens")}
+    for li, layer in enumerate(rot.layers):
+        trace = torch.zeros(n_slots * S, dtype=torch.int64, device="cuda")
+        rot.layers[li - 1].run()                      # keeps the pipeline as in a running rotation
+        layer.run(trace=trace)
+        torch.cuda.synchronize()
+        t = trace.cpu().numpy().reshape(n_slots, S).astype(np.float64)
+        used = t[:, 0] > 0
+        t0 = t[used, 0].min()
+        us = np.where(t > 0, (t - t0) / 100.0, np.nan)          # 100 MHz wall clock
+        per_layer.append(us)
+        pl = layer.plan
+        cnt = np.diff(pl.slot_ptr)
+        rows["n_items"].append(cnt)
+        rows["tokens"].append(np.array([pl.items["tok_count"][pl.slot_ptr[j]:pl.slot_ptr[j + 1]].sum() for j in range(n_slots)]))
+        rows["has_handover"].append(~np.isnan(us[:, 6]))
+        rows["merges"].append((us[:, 9] - us[:, 8]) > 0.15)
+    us = np.stack(per_layer)                                      # [layers, slots, stamps]
+    q = lambda x, p: float(np.nanpercentile(x, p))
+    table = {}
+    for k, nm in enumerate(names):
+        col = us[:, :, k]
+        table[nm] = {"median": round(q(col, 50), 2), "p90": round(q(col, 90), 2), "max_mean_over_layers": round(float(np.nanmean(np.nanmax(col, axis=1))), 2)}
+    ho = np.concatenate([u[:, 10] - u[:, 6] for u in per_layer])
+    merged = np.concatenate(rows["merges"])
+    has = np.concatenate(rows["has_handover"])
+    span = float(np.mean([np.nanmax(u[:, 11]) for u in per_layer]))
+    stream_end = np.stack([u[:, 5] for u in per_layer])
+    rec = {"experiment": "phases of one launch by the GPU's 100 MHz wall clock (fairkv_decode_attn_trace), microseconds "
+                         "since the launch's first stamp; per workgroup, pooled over the layers",
+           "workload": w_name, "layers": len(rot.layers), "n_slots": n_slots, "stamps": table,
+           "launch_span_us_mean": round(span, 2),
+           "last_item_streamed_spread_us": {"p10": round(q(stream_end, 10), 2), "median": round(q(stream_end, 50), 2),
+                                            "p90": round(q(stream_end, 90), 2), "max_mean": round(float(np.nanmean(np.nanmax(stream_end, axis=1))), 2)},
+           "hand_over_us": {"workgroups_with_one": int(has.sum()), "that_merged": int((merged & has).sum()),
+                            "median_no_merge": round(q(ho[has & ~merged], 50), 2) if (has & ~merged).any() else None,
+                            "median_merge": round(q(ho[has & merged], 50), 2) if (has & merged).any() else None,
+                            "p90_merge": round(q(ho[has & merged], 90), 2) if (has & merged).any() else None},
+           "steps_of_the_hand_over_us_median": {
+               "publish (issue stores)": round(q(np.concatenate([u[:, 7] - u[:, 6] for u in per_layer]), 50), 2),
+               "count in (one atomic round trip)": round(q(np.concatenate([u[:, 8] - u[:, 7] for u in per_layer]), 50), 2),
+               "merge, for those that merge": round(q(np.concatenate([u[:, 9] - u[:, 8] for u in per_layer])[merged & has], 50), 2) if (merged & has).any() else None},
+           }
+    n_items = np.concatenate(rows["n_items"])
+    dur = np.concatenate([u[:, 11] - u[:, 0] for u in per_layer])
+    rec["by_items_in_slot"] = {str(int(k)): {"slots": int((n_items == k).sum()), "median_us": round(q(dur[n_items == k], 50), 2),
+                                             "median_tokens": int(np.median(np.concatenate(rows["tokens"])[n_items == k]))}
+                               for k in np.unique(n_items) if (n_items == k).sum() >= 8}
+    return rec
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -513,8 +656,6 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": n, "copies": 3}))
         return
-    if os.environ.get("FAIRKV_LIB"):        # A/B runs against another build of the library
-        F.LIB_PATH = os.environ["FAIRKV_LIB"]
     F.lib()
     if a.latency_model:
         print(json.dumps(latency_model(a.seed)))
@@ -529,12 +670,18 @@ def main():
     n_layers = a.layers or w.n_layers
     overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens")
                  if getattr(a, k) is not None}
+    if a.phases:
+        print(json.dumps(phases(a, overrides)))
+        return
     kv8 = a.kv_dtype == "fp8"
+    valu = a.bf16_kernel == "valu"
+    if valu:
+        a.no_extras = True
     if kv8:
         a.no_extras = True      # the comparisons and the CPU baseline belong to the headline configuration
         # half the bytes per token: the planner's per-item overhead is worth twice the tokens, and a step is 32 tokens
         overrides = {**KV8_PLAN_DEFAULTS, **overrides}
-    rot = Rotation(a.workload, n_layers, a.seed, a.policy, overrides, a.q_len, kv8)
+    rot = Rotation(a.workload, n_layers, a.seed, a.policy, overrides, a.q_len, kv8, valu)
     host_s, ev_s, moved = timed(rot, a.steps, a.warmup, not a.no_graph)
     gbs = moved / ev_s / 1e9
     ms_step = 1e3 * ev_s / a.steps
@@ -547,19 +694,28 @@ def main():
         "metric": "achieved HBM GB/s, ragged per-head GQA decode attention (algorithmic bytes / time)",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.description}", "storage": "e4m3 K/V, bf16 q" if kv8 else w.dtype, "B": w.B, "q_len": a.q_len, "Hq": w.Hq, "Hkv": w.Hkv,
+        "dtype": "bf16 (fp32 accumulate)" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "shape": w.description,
+                   "storage": "e4m3 K/V, bf16 q" if kv8 else w.dtype, "B": w.B, "q_len": a.q_len, "Hq": w.Hq, "Hkv": w.Hkv,
                    "D": w.D, "layers_rotated": n_layers, "rotation_GB": round(sum(rot.bytes) / 1e9, 3),
                    "policy": a.policy, "n_slots": int(rot.params.n_slots), "min_chunk": int(rot.params.min_chunk),
                    "oversub": int(rot.params.oversub), "graph_replay": not a.no_graph,
+                   "timed_region": (f"HIP graph replays only: {a.steps // n_layers} x a graph of {n_layers} launches"
+                                    + (f" + 1 x a graph of {a.steps % n_layers} launches" if a.steps % n_layers else ""))
+                   if not a.no_graph else f"{a.steps} launches enqueued from Python",
+                   "kernel": "vector ALU (A/B run)" if valu else "matrix cores",
                    "items_layer0": plan0.n_items},
         "us_per_layer": round(1e3 * ms_step, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "host_clock_GBs": round(moved / host_s / 1e9, 1),
         "plan_host_us_per_layer": round(rot.plan_us, 1),
         "plan_layer0": {"max_slot_load": loads_max, "min_slot_load": loads_min, "efficiency_E": round(eff0, 4)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None if kv8 else measured_traffic(a.workload),
-                     "kernel": f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}, DEEP, {'true' if kv8 else 'false'}>",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None if (kv8 or valu or a.q_len > 1) else measured_traffic(a.workload)[0],
+                     "traffic_source": None if (kv8 or valu or a.q_len > 1) else
+                     f"not measured in this run: read from {measured_traffic(a.workload)[1]} (rocprofv3 FETCH_SIZE and WRITE_SIZE)",
+                     "kernel": f"fairkv_decode_valu_kernel<bf16, {w.D}, {w.G}>" if valu else
+                     f"fairkv_decode_mfma_kernel<{w.D}, {w.G * a.q_len}, DEEP, {'true' if kv8 else 'false'}>",
                      "bytes_per_launch": round(moved / a.steps), "us_per_launch": round(1e3 * ms_step, 3)},
         "paper_context": "FairKV reports up to 1.66x throughput over plain tensor parallelism on 8x A100-80G "
                          "(Llama-3.3-70B, Section 5.2.2); other hardware, not this metric",
@@ -580,6 +736,10 @@ def main():
             del r2
             torch.cuda.empty_cache()
         rec["stream_probe"] = stream_probe(rot, gbs)
+        rec["uniform_same_bytes"] = uniform_same_bytes(rot, a.seed)
+        rec["probe_uniform_ragged_us"] = [rec["stream_probe"]["us_per_layer"], rec["uniform_same_bytes"]["us_per_layer"],
+                                          rec["us_per_layer"]]
+        rec["workloads"] = other_workloads(a, overrides)
         rec["cold_single_launch_us"] = cold_launch_us(rot)
         rec["lpt_equal_split_GBs_by_max_split"] = max_split_sweep(a, n_layers, overrides, gbs)
         rec["cpu_baseline"] = cpu_baseline(rot, a.cpu_seconds)

@@ -49,8 +49,11 @@ typedef enum {
 } fairkv_status;
 
 enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1,
-       FAIRKV_E4M3 = 2 /* one byte per element: fairkv_pack and fairkv_append only (they move bytes) */ };
-enum { FAIRKV_MAX_SLOTS = 320 };   /* most slots a plan handed to fairkv_decode_attn may have */
+       FAIRKV_E4M3 = 2, /* one byte per element: fairkv_pack and fairkv_append only (they move bytes) */
+       FAIRKV_BF16_VALU = 3 /* in_dtype of fairkv_decode_attn only: bf16 inputs through the vector-ALU kernel that
+                               serves fp32 instead of the matrix-core kernel; for A/B measurements of the two */ };
+enum { FAIRKV_MAX_SLOTS = 320 };   /* most workgroups fairkv_decode_attn launches; a plan with more slots is run with
+                                      consecutive slots sharing a workgroup */
 
 /* How the work list is built; the four mirror the paper's ablation (Section 5.2.1).
  *   NAIVE      pairs dealt to slots round-robin in (b, h) order, unsplit: the analogue of the
@@ -143,8 +146,10 @@ int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, int32_t Hkv, 
  * Layout: the counters first (fairkv_workspace_counter_bytes(n_pairs) bytes: one per pair and
  * one per group of 8 pieces of a pair cut 32 ways or more; their number depends on n_pairs alone),
  * then statistics and partial outputs.  The counter bytes must be zero before the first use;
- * every completed call leaves them zero again, whatever its plan, so calls with the same
- * B * Hkv that are ordered on one stream may share one workspace. */
+ * every completed call leaves them zero again, whatever its plan, so calls that are ordered on
+ * one stream may share one workspace (the counter region of a smaller B * Hkv is a prefix of a
+ * larger one's).  After a launch that did not complete (an aborted process, a device reset) zero
+ * the counter bytes again: nothing else in the workspace carries state from call to call. */
 size_t fairkv_workspace_counter_bytes(int32_t n_pairs);
 size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D);
 
@@ -170,20 +175,22 @@ size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32
  * slot_ptr   HOST [n_slots+1]: the plan's slot pointer.  The slot pointer and the first item
  *            of every slot travel to the GPU inside the kernel arguments, so that a workgroup
  *            requests its first K/V rows without first fetching its item list (two memory
- *            round trips less at the start of a 20 us kernel); this limits n_slots to
- *            FAIRKV_MAX_SLOTS.  items_host is also checked: every item must name a pair of
- *            this problem, rows >= 0 and a partial slot below n_parts (else FAIRKV_EINVAL).
+ *            round trips less at the start of a 20 us kernel); with more than
+ *            FAIRKV_MAX_SLOTS slots, consecutive slots share a workgroup.  items_host is also
+ *            checked: every item must name a pair of this problem, rows >= 0 and a partial slot
+ *            below n_parts, and a cut pair must come with every one of its n_chunks pieces, each
+ *            once, in consecutive partial slots (else FAIRKV_EINVAL).
  * workspace  device, at least fairkv_workspace_bytes(n_parts, B*Hkv, G, D) bytes, 16-byte
- *            aligned, zero-filled before its first use (see fairkv_workspace_bytes)
+ *            aligned, its counter bytes zero before the first use (see fairkv_workspace_bytes)
  * out        device [B][Hq][D], element type out_dtype (FAIRKV_F32, or FAIRKV_BF16 rounded
  *            to nearest even), 16-byte aligned
  * lse        device [B][Hq] float, or NULL
  * scale      multiplies the scores (1/sqrt(D) in the usual models)
  * hip_stream a hipStream_t (NULL = the default stream)
  *
- * Supported: D in {64, 128}; in_dtype BF16 or F32; G = Hq/Hkv in {1, 2, 4, 8};
- * n_slots <= FAIRKV_MAX_SLOTS (else FAIRKV_EUNSUPPORTED).
- * Calls that share a workspace must have the same B * Hkv and be ordered on one stream.
+ * Supported: D in {64, 128}; in_dtype BF16 or F32 (or BF16_VALU); G = Hq/Hkv in {1, 2, 4, 8}
+ * (else FAIRKV_EUNSUPPORTED).
+ * Calls that share a workspace must be ordered on one stream.
  */
 int fairkv_decode_attn(const void *q, const void *k, const void *v, int64_t n_rows,
                        const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
@@ -338,6 +345,22 @@ int fairkv_append(const void *k_new, const void *v_new, int32_t B, int32_t Hkv, 
  * last chunk per pair).  The plan stays valid and drifts from balance by at most one row per pair
  * and step; re-plan with fairkv_plan every few hundred steps. */
 int fairkv_plan_grow(fairkv_item *items, int32_t n_items, int32_t B, int32_t Hkv, int32_t *len, const int32_t *cap);
+
+/* Measurement aid, not part of the method: fairkv_decode_attn (bf16 in, fp32 out, D = 128, G = 4 or 8, plans
+ * without a pair in 32 pieces or more; else FAIRKV_EUNSUPPORTED) through an instantiation of the same kernel
+ * that also stamps the phases of every workgroup with the GPU's 100 MHz wall clock.
+ * trace: device, FAIRKV_TRACE_STAMPS uint64 per workgroup (trace_bytes >= n_slots * FAIRKV_TRACE_STAMPS * 8, else
+ * FAIRKV_EINVAL), zero-filled by the caller; stamp k of workgroup j is trace[j * FAIRKV_TRACE_STAMPS + k]:
+ * 0 first instruction, 1 item list landed and checked, 2 first K/V tile landed, 3 first item streamed (wave 0),
+ * 4 first item folded and written, 5 last item streamed (wave 0), 6 hand-over begins, 7 partial results' stores
+ * issued, 8 counted in, 9 merges done, 10 hand-over ends (6-10: the workgroup's last hand-over; 0 if it had none),
+ * 11 last instruction.  bench.py --phases turns one launch's stamps into the phase table under profiles/. */
+enum { FAIRKV_TRACE_STAMPS = 16 };
+int fairkv_decode_attn_trace(const void *q, const void *k, const void *v, int64_t n_rows,
+                             const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                             const int32_t *slot_ptr, int32_t n_slots, int32_t n_parts, void *workspace,
+                             size_t workspace_bytes, void *out, float *lse, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                             float scale, uint64_t *trace, size_t trace_bytes, void *hip_stream);
 
 /* Measurement aid, not part of the method: n_workgroups workgroups stream the first bytes_each
  * bytes (rounded down to a multiple of 4096 * n_workgroups) of the device buffers k and v from HBM

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfairkv.so")
 
 FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, FAIRKV_EHIP = 0, -1, -2, -3, -4, -5
-FAIRKV_BF16, FAIRKV_F32, FAIRKV_E4M3 = 0, 1, 2
+FAIRKV_BF16, FAIRKV_F32, FAIRKV_E4M3, FAIRKV_BF16_VALU = 0, 1, 2, 3
+FAIRKV_TRACE_STAMPS = 16
 FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
@@ -25,6 +26,7 @@ FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_workspace_counter_bytes",
            "fairkv_decode_attn",
            "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8", "fairkv_decode_attn_kv8_per_head",
+           "fairkv_decode_attn_trace",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
@@ -117,6 +119,9 @@ def lib() -> ctypes.CDLL:
         L.fairkv_decode_attn_kv8_per_head.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, vp, vp, i32, vp,
                                                       i32, i32, vp, ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32,
                                                       ctypes.c_float, vp]
+        L.fairkv_decode_attn_trace.restype = ctypes.c_int
+        L.fairkv_decode_attn_trace.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t,
+                                               vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.fairkv_strerror.restype = ctypes.c_char_p
         L.fairkv_strerror.argtypes = [ctypes.c_int]
         L.fairkv_version.restype = ctypes.c_int
@@ -229,8 +234,12 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None):
+def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace, out, lse, scale, Hkv, stream=None,
+                       bf16_on_valu=False, trace=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
+
+    trace (a zero-filled int64 device tensor of n_slots * FAIRKV_TRACE_STAMPS) calls fairkv_decode_attn_trace;
+    bf16_on_valu passes FAIRKV_BF16_VALU.
 
     Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D], or [B,q_len,Hq,D] for
     several new tokens per sequence (fairkv_decode_attn_multi; out and lse then carry q_len too); k, v [rows,D];
@@ -249,7 +258,7 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
     if q.dtype not in dt or k.dtype != q.dtype or v.dtype != q.dtype or out.dtype not in dt:
         raise TypeError("q/k/v must share bf16 or fp32; out must be bf16 or fp32")
     for name, t in (("q", q), ("k", k), ("v", v), ("items", items), ("workspace", workspace), ("out", out),
-                    ("lse", lse)):
+                    ("lse", lse), ("trace", trace)):
         if t is None:
             continue
         if not t.is_cuda or not t.is_contiguous():
@@ -270,14 +279,22 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
         raise TypeError("items_host must be the plan's contiguous item array, as many records as `items`")
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
-    rc = lib().fairkv_decode_attn_multi(
-        _ptr(q), _ptr(k), _ptr(v), k.shape[0], _ptr(items), items_host.ctypes.data, item_bytes // 32, slot_ptr.ctypes.data,
-        slot_ptr.size - 1,
-        int(n_parts), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, dt[q.dtype], dt[out.dtype], float(scale),
-        ctypes.c_void_p(stream.cuda_stream))
+    in_dt = FAIRKV_BF16_VALU if (bf16_on_valu and q.dtype == torch.bfloat16) else dt[q.dtype]
+    head = (_ptr(q), _ptr(k), _ptr(v), k.shape[0], _ptr(items), items_host.ctypes.data, item_bytes // 32,
+            slot_ptr.ctypes.data, slot_ptr.size - 1, int(n_parts))
+    st = ctypes.c_void_p(stream.cuda_stream)
+    if trace is not None:
+        if q_len != 1 or trace.dtype != torch.int64:
+            raise ValueError("a traced call is a single-token call with an int64 trace buffer")
+        name = "fairkv_decode_attn_trace"
+        rc = lib().fairkv_decode_attn_trace(*head, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out),
+                                            _ptr(lse), B, Hq, Hkv, D, float(scale), _ptr(trace), trace.numel() * 8, st)
+    else:
+        name = "fairkv_decode_attn_multi" if q_len > 1 else "fairkv_decode_attn"
+        rc = lib().fairkv_decode_attn_multi(*head, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out),
+                                            _ptr(lse), B, q_len, Hq, Hkv, D, in_dt, dt[out.dtype], float(scale), st)
     if rc != FAIRKV_OK:
-        raise FairKVError(rc, "fairkv_decode_attn_multi" if q_len > 1 else "fairkv_decode_attn")
+        raise FairKVError(rc, name)
 
 
 def fairkv_decode_attn_kv8(q, k8, v8, k_scale, v_scale, items, items_host, slot_ptr, n_parts, workspace, out, lse,

@@ -109,7 +109,30 @@ struct DecodeArgs {
     uint32_t first_row[FAIRKV_MAX_SLOTS];     // first K/V row of slot j's first item ...
     uint32_t first_np[FAIRKV_MAX_SLOTS];      // ... its pair b*Hkv+h in bits 9..31 and min(tok_count, kEarlyTok) in
                                               // bits 0..8; 0 = no early start for this slot
+    unsigned long long *trace;                // fairkv_decode_attn_trace only: [workgroups][kTraceStamps], else null
 };
+
+// Phases a traced launch stamps with the 100 MHz wall clock, per workgroup (thread 0 of wave 0).  A stamp
+// keeps its latest value: the hand-over stamps are those of the workgroup's last hand-over.
+enum {
+    kTraceStart = 0,         // first instruction
+    kTraceTable,             // item list landed and checked
+    kTraceFirstTile,         // first K/V tile landed
+    kTraceItem0Streamed,     // wave 0 has consumed its tiles of the first item
+    kTraceItem0Done,         // first item folded and written (or kept pending)
+    kTraceLastStreamed,      // wave 0 has consumed its tiles of the last item
+    kTraceFlushBegin,        // hand-over: all waves are there
+    kTraceFlushPublished,    // partials' stores issued
+    kTraceFlushCounted,      // count-in returned, roles known
+    kTraceFlushMerged,       // merges (if any) computed and written
+    kTraceFlushEnd,
+    kTraceEnd,               // last instruction
+    kTraceStamps = 16
+};
+__device__ __forceinline__ void trace_stamp(const DecodeArgs &a, int what, bool who)
+{
+    if (a.trace && who) a.trace[static_cast<size_t>(blockIdx.x) * kTraceStamps + what] = wall_clock64();
+}
 constexpr int kEarlyTok = 256;            // tokens of a slot's first item that the early start may request
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
@@ -376,10 +399,11 @@ __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D,
 // DEEP: the plan has a pair in kDeepFrom pieces or more.  Without it the group code is not even compiled
 // in: on the headline workload its mere presence cost 0.8 us per launch (longer cold code on the
 // critical tail, more registers in the main loop).
-template <int D, int G, bool DEEP>
+template <int D, int G, bool DEEP, bool TRACE = false>
 __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<D, G> &pend, int &n_pend)
 {
     __syncthreads();
+    if constexpr (TRACE) trace_stamp(a, kTraceFlushBegin, threadIdx.x == 0);
     for (int p = 0; p < n_pend; ++p) {
         const size_t base = static_cast<size_t>(pend.part[p]) * G;
         for (int idx = threadIdx.x; idx < G * D / 4; idx += kThreads)
@@ -388,6 +412,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
     }
     drain_vmem();                                      // this thread's stores have reached the shared level ...
     __syncthreads();                                   // ... and every other thread's, before the workgroup counts itself in
+    if constexpr (TRACE) trace_stamp(a, kTraceFlushPublished, threadIdx.x == 0);
     // Round 0: every pending piece counts in (a piece of a deeply cut pair on its group's counter) and
     // the last arrivals merge.  Round 1, only if this workgroup merged a group: that group counts in on
     // the pair's counter.  One copy of the merge code serves both rounds: the hand-over runs once per
@@ -426,7 +451,9 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
             pend.role[p] = role;
         }
         __syncthreads();
+        if constexpr (TRACE) trace_stamp(a, kTraceFlushCounted, threadIdx.x == 0);
         merge_round<D, G, DEEP>(a, pend, n_pend);
+        if constexpr (TRACE) trace_stamp(a, kTraceFlushMerged, threadIdx.x == 0);
         bool any_group = false;
         if (DEEP)
             for (int p = 0; p < n_pend; ++p) any_group |= pend.role[p] == kRoleGroup;
@@ -439,6 +466,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
     n_pend = 0;
     drain_vmem();     // the compiler stops tracking the loads above: no guard waits on their registers later on
     __syncthreads();
+    if constexpr (TRACE) trace_stamp(a, kTraceFlushEnd, threadIdx.x == 0);
 }
 
 // End of one item, called by all threads of the workgroup after every wave has put its
@@ -447,7 +475,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
 //   m* = max_w m_w,  l* = sum_w l_w 2^(m_w - m*),  o* = sum_w o_w 2^(m_w - m*).
 // An item that is a whole pair writes out = o*/l* and lse.  An item of a cut pair leaves its
 // partial (m*, l*, o*) in `pend`.  Ends with a barrier, so st_o/st_ml may be reused at once.
-template <int D, int G, bool DEEP>
+template <int D, int G, bool DEEP, bool TRACE = false>
 __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_item &it, const float *st_o,
                                               const float *st_ml, PendingParts<D, G> &pend, int &n_pend, float v_mul)
 {
@@ -503,7 +531,7 @@ __device__ __forceinline__ void item_epilogue(const DecodeArgs &a, const fairkv_
         }
         ++n_pend;
         if (n_pend == pend_slots(D, G)) {
-            flush_pending<D, G, DEEP>(a, pend, n_pend);
+            flush_pending<D, G, DEEP, TRACE>(a, pend, n_pend);
             return;
         }
     }

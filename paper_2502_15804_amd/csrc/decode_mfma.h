@@ -130,7 +130,9 @@ constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches
 //                      8-bit transposing read: lane i of a 16-lane group addresses the 8 bytes (token
 //                      t_(i/2), columns 8 (i%2) .. +7) and lane j receives byte j%8 of the fragments
 //                      j/8, j/8 + 2, ..., i.e. column j of tokens t_0 .. t_7 (layout checked on the GPU).
-template <int D, int G, bool DEEP, bool KV8>
+// TRACE: the measurement instantiation behind fairkv_decode_attn_trace; it writes wall-clock stamps of its phases
+// (see trace_stamp) and is otherwise the same code.
+template <int D, int G, bool DEEP, bool KV8, bool TRACE = false>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
@@ -169,6 +171,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     const int l16 = lane & 15;      // head in B/C operands, token row in the K operand, d in the V operand
     const int lq = lane >> 4;       // which quarter of the contraction index this lane feeds
 
+    if constexpr (TRACE) trace_stamp(a, kTraceStart, threadIdx.x == 0);
     const int i_begin = a.slot_ptr[blockIdx.x], i_end = a.slot_ptr[blockIdx.x + 1];
     if (i_end <= i_begin) return;   // an idle slot
     if constexpr (KV8) {
@@ -338,6 +341,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                                           it.chunk, it.n_chunks, it.part, {0, 0, 0}};
         }
         __syncthreads();
+        if constexpr (TRACE)
+            if (batch == i_begin) trace_stamp(a, kTraceTable, threadIdx.x == 0);
 
         auto seek = [&](int item) {           // point the fetch cursor at an item of the table
             f_item = item;
@@ -403,6 +408,8 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 // tiles in the ring and their query blocks.
                 wait_all_but<LOADS, QL>(ahead - 1, __builtin_popcount(q_mask & ~(1u << c_stage)));
                 q_mask &= ~(1u << c_stage);
+                if constexpr (TRACE)
+                    if (batch == i_begin && ci == 0 && t == 0) trace_stamp(a, kTraceFirstTile, threadIdx.x == 0);
                 if (t == 0) {
                     // q as the B operand of the score MFMA: lane holds q[head l16][32 s + 8 lq .. +8].  Heads
                     // >= G repeat head G-1: their columns of the products are computed and never stored.
@@ -541,6 +548,10 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 --ahead;
             }
 
+            if constexpr (TRACE) {
+                if (batch == i_begin && ci == 0) trace_stamp(a, kTraceItem0Streamed, threadIdx.x == 0);
+                if (batch + ci == i_end - 1) trace_stamp(a, kTraceLastStreamed, threadIdx.x == 0);
+            }
             // ---- fold the four token quarters of l, stage this wave's result, finish the item ------
             l_run += __shfl_xor(l_run, 16, 64);
             l_run += __shfl_xor(l_run, 32, 64);
@@ -554,11 +565,14 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                     st_ml[(wave * G + l16) * 2 + 1] = l_run;
                 }
             }
-            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G, DEEP>(a, it, st_o, st_ml, pend, n_pend, v_mul);
+            if (__builtin_amdgcn_readfirstlane(table[ci].valid)) item_epilogue<D, G, DEEP, TRACE>(a, it, st_o, st_ml, pend, n_pend, v_mul);
+            if constexpr (TRACE)
+                if (batch == i_begin && ci == 0) trace_stamp(a, kTraceItem0Done, threadIdx.x == 0);
         }
         wait_vmcnt<0>();   // nothing of this batch may still be landing in the rings
     }
-    if (n_pend > 0) flush_pending<D, G, DEEP>(a, pend, n_pend);
+    if (n_pend > 0) flush_pending<D, G, DEEP, TRACE>(a, pend, n_pend);
+    if constexpr (TRACE) trace_stamp(a, kTraceEnd, threadIdx.x == 0);
 }
 
 }  // namespace fairkv

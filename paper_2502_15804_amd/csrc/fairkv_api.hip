@@ -12,6 +12,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <vector>
 
 #include "decode_mfma.h"
 #include "decode_valu.h"
@@ -37,6 +38,18 @@ hipError_t launch_valu(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
     return hipGetLastError();
 }
 
+// The measurement instantiation exists for the shapes the benchmark traces: D = 128, bf16, plans without deeply cut pairs.
+hipError_t launch_mfma_trace(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
+{
+    const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
+    switch (G) {
+    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 4, false, false, true>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 8, false, false, true>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int D, bool DEEP, bool KV8>
 hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
 {
@@ -54,28 +67,22 @@ hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// FAIRKV_BF16_KERNEL=valu sends bf16 inputs through the vector-ALU kernel (for A/B
-// measurements of the two kernels); anything else, or unset, uses the matrix-core kernel.
-bool bf16_on_valu()
-{
-    static const bool v = [] {
-        const char *e = std::getenv("FAIRKV_BF16_KERNEL");
-        return e && e[0] == 'v';
-    }();
-    return v;
-}
-
 }  // namespace
 
 namespace {
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Partial-result slots of a plan with n_parts items: one per item (a group partial of a pair cut very deeply
+// takes the slot of the group's first piece).
+size_t part_slots(int32_t n_parts) { return static_cast<size_t>(n_parts); }
+
 }  // namespace
 
-// Workspace layout: counters | part_ml [n_parts][G][2] f32 | part_o [n_parts][G][D] f32, each region
-// starting on a 256-byte boundary.  The counters come first so that their place does not depend on
-// n_parts: calls with different plans may then share one workspace.
+// Workspace layout: counters | part_ml [slots][G][2] f32 | part_o [slots][G][D] f32, each region
+// starting on a 256-byte boundary, slots = part_slots(n_parts).  The counters come first so that their place
+// does not depend on n_parts: calls with different plans may then share one workspace.  The counters are zero
+// between calls.
 // Counters of the hand-over: one per pair, then one per group of a pair cut into many pieces (indexed
 // by the pair's first partial slot plus the group; a line cut has fewer partial slots than pairs plus
 // slots, so n_pairs + FAIRKV_MAX_SLOTS counters serve every such plan).  Their number depends on the
@@ -89,9 +96,53 @@ extern "C" size_t fairkv_workspace_counter_bytes(int32_t n_pairs)
 extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D)
 {
     if (n_parts < 0 || n_pairs < 1 || G < 1 || D < 1) return 0;
-    return align256(static_cast<size_t>(n_parts) * G * D * sizeof(float)) +
-           align256(static_cast<size_t>(n_parts) * G * 2 * sizeof(float)) + fairkv_workspace_counter_bytes(n_pairs);
+    return align256(part_slots(n_parts) * G * D * sizeof(float)) + align256(part_slots(n_parts) * G * 2 * sizeof(float)) +
+           fairkv_workspace_counter_bytes(n_pairs);
 }
+
+namespace {
+
+// Everything a decode call is given; the entry points differ in where the workspace comes from and in what they
+// add (8-bit scales, a trace buffer).
+struct DecodeCall {
+    const void *q, *k, *v;
+    int64_t n_rows;
+    const fairkv_item *items, *items_host;
+    int32_t n_items;
+    const int32_t *slot_ptr;
+    int32_t n_slots, n_parts;
+    void *workspace;
+    size_t workspace_bytes;
+    void *out;
+    float *lse;
+    int32_t B, q_len, Hq, Hkv, D, in_dtype, out_dtype;
+    float scale;
+    bool kv8 = false;
+    float k_scale = 1.f, v_scale = 1.f;
+    const float *k_head = nullptr, *v_head = nullptr;
+    unsigned long long *trace = nullptr;
+    void *hip_stream;
+};
+
+int decode_common(const DecodeCall &c);
+
+DecodeCall make_call(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
+                     const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
+                     int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
+                     int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
+                     void *hip_stream)
+{
+    DecodeCall c{};
+    c.q = q; c.k = k; c.v = v; c.n_rows = n_rows; c.items = items; c.items_host = items_host; c.n_items = n_items;
+    c.slot_ptr = slot_ptr; c.n_slots = n_slots; c.n_parts = n_parts; c.workspace = workspace;
+    c.workspace_bytes = workspace_bytes; c.out = out; c.lse = lse; c.B = B; c.q_len = q_len; c.Hq = Hq; c.Hkv = Hkv;
+    c.D = D; c.in_dtype = in_dtype; c.out_dtype = out_dtype; c.scale = scale; c.hip_stream = hip_stream;
+    return c;
+}
+
+bool finite(float x) { return x == x && !std::isinf(x); }
+
+}  // namespace
 
 extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
                                   const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr,
@@ -101,17 +152,9 @@ extern "C" int fairkv_decode_attn(const void *q, const void *k, const void *v, i
                                   int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
                                   void *hip_stream)
 {
-    return fairkv_decode_attn_multi(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
-                                    workspace_bytes, out, lse, B, 1, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream);
+    return decode_common(make_call(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                                   workspace_bytes, out, lse, B, 1, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream));
 }
-
-namespace {
-int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
-                  const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
-                  int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
-                  int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
-                  bool kv8, float k_scale, float v_scale, const float *k_head, const float *v_head, void *hip_stream);
-}  // namespace
 
 extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void *v, int64_t n_rows,
                                         const fairkv_item *items,
@@ -120,9 +163,8 @@ extern "C" int fairkv_decode_attn_multi(const void *q, const void *k, const void
                                         void *out, float *lse, int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv,
                                         int32_t D, int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream)
 {
-    return decode_common(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
-                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, in_dtype, out_dtype, scale, false, 1.f, 1.f,
-                         nullptr, nullptr, hip_stream);
+    return decode_common(make_call(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                                   workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, in_dtype, out_dtype, scale, hip_stream));
 }
 
 extern "C" int fairkv_decode_attn_kv8(const void *q, const void *k8, const void *v8, int64_t n_rows, float k_scale,
@@ -132,10 +174,13 @@ extern "C" int fairkv_decode_attn_kv8(const void *q, const void *k8, const void 
                                       int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t out_dtype, float scale,
                                       void *hip_stream)
 {
-    if (!(k_scale == k_scale) || !(v_scale == v_scale) || std::isinf(k_scale) || std::isinf(v_scale)) return FAIRKV_EINVAL;
-    return decode_common(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
-                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, true, k_scale,
-                         v_scale, nullptr, nullptr, hip_stream);
+    if (!finite(k_scale) || !finite(v_scale)) return FAIRKV_EINVAL;
+    DecodeCall c = make_call(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                             workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, hip_stream);
+    c.kv8 = true;
+    c.k_scale = k_scale;
+    c.v_scale = v_scale;
+    return decode_common(c);
 }
 
 extern "C" int fairkv_decode_attn_kv8_per_head(const void *q, const void *k8, const void *v8, int64_t n_rows,
@@ -148,70 +193,103 @@ extern "C" int fairkv_decode_attn_kv8_per_head(const void *q, const void *k8, co
     if (!k_scale || !v_scale || Hkv < 1) return FAIRKV_EINVAL;
     if (Hkv > kScaleHeads) return FAIRKV_EUNSUPPORTED;
     for (int32_t h = 0; h < Hkv; ++h)
-        if (!(k_scale[h] == k_scale[h]) || !(v_scale[h] == v_scale[h]) || std::isinf(k_scale[h]) || std::isinf(v_scale[h]))
-            return FAIRKV_EINVAL;
-    return decode_common(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
-                         workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, true, 1.f, 1.f,
-                         k_scale, v_scale, hip_stream);
+        if (!finite(k_scale[h]) || !finite(v_scale[h])) return FAIRKV_EINVAL;
+    DecodeCall c = make_call(q, k8, v8, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                             workspace_bytes, out, lse, B, q_len, Hq, Hkv, D, FAIRKV_BF16, out_dtype, scale, hip_stream);
+    c.kv8 = true;
+    c.k_head = k_scale;
+    c.v_head = v_scale;
+    return decode_common(c);
+}
+
+extern "C" int fairkv_decode_attn_trace(const void *q, const void *k, const void *v, int64_t n_rows,
+                                        const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                                        const int32_t *slot_ptr, int32_t n_slots, int32_t n_parts, void *workspace,
+                                        size_t workspace_bytes, void *out, float *lse, int32_t B, int32_t Hq, int32_t Hkv,
+                                        int32_t D, float scale, uint64_t *trace, size_t trace_bytes, void *hip_stream)
+{
+    if (!trace || n_slots < 1 || trace_bytes < static_cast<size_t>(n_slots) * kTraceStamps * sizeof(uint64_t)) return FAIRKV_EINVAL;
+    if (D != 128 || Hkv < 1 || (Hq != 8 * Hkv && Hq != 4 * Hkv) || n_slots > FAIRKV_MAX_SLOTS) return FAIRKV_EUNSUPPORTED;
+    DecodeCall c = make_call(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, workspace,
+                             workspace_bytes, out, lse, B, 1, Hq, Hkv, D, FAIRKV_BF16, FAIRKV_F32, scale, hip_stream);
+    c.trace = reinterpret_cast<unsigned long long *>(trace);
+    return decode_common(c);
 }
 
 namespace {
-int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, const fairkv_item *items,
-                  const fairkv_item *items_host, int32_t n_items, const int32_t *slot_ptr, int32_t n_slots,
-                  int32_t n_parts, void *workspace, size_t workspace_bytes, void *out, float *lse, int32_t B,
-                  int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype, int32_t out_dtype, float scale,
-                  bool kv8, float k_scale, float v_scale, const float *k_head, const float *v_head, void *hip_stream)
+int decode_common(const DecodeCall &c)
 {
-    if (!q || !k || !v || !items || !items_host || !slot_ptr || !out) return FAIRKV_EINVAL;
-    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1 || n_rows < 0) return FAIRKV_EINVAL;
+    const int32_t B = c.B, Hq = c.Hq, Hkv = c.Hkv, D = c.D, q_len = c.q_len, n_items = c.n_items, n_slots = c.n_slots,
+                  n_parts = c.n_parts;
+    const fairkv_item *items_host = c.items_host;
+    const int32_t *slot_ptr = c.slot_ptr;
+    if (!c.q || !c.k || !c.v || !c.items || !items_host || !slot_ptr || !c.out) return FAIRKV_EINVAL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || n_items < 1 || n_slots < 1 || n_parts < 0 || q_len < 1 || c.n_rows < 0) return FAIRKV_EINVAL;
     if (Hq % Hkv != 0) return FAIRKV_EINVAL;
     if (n_parts < n_items) return FAIRKV_EINVAL;
-    if (n_slots > FAIRKV_MAX_SLOTS) return FAIRKV_EUNSUPPORTED;
     if (slot_ptr[0] != 0 || slot_ptr[n_slots] != n_items) return FAIRKV_EINVAL;
     for (int32_t j = 0; j < n_slots; ++j)
         if (slot_ptr[j] > slot_ptr[j + 1]) return FAIRKV_EINVAL;
+    // Every cut pair must come with all its pieces, each exactly once: a piece that is missing would leave the
+    // pair's arrival counter short for ever (no output, and a counter that is not zero for the next call); one
+    // that comes twice would have two workgroups write one partial slot.  count[first slot of a pair] counts
+    // that pair's pieces; a piece's own slot must be used once.
+    std::vector<int32_t> count(static_cast<size_t>(n_parts), 0);
     bool deep = false;      // a pair in very many pieces: the kernel with the two-level merge
     for (int32_t i = 0; i < n_items; ++i) {
         const fairkv_item &it = items_host[i];
         deep |= it.n_chunks >= kDeepFrom;
         if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
-        if (it.row + it.tok_count > n_rows) return FAIRKV_EINVAL;      // the kernel reads exactly these rows of K and V
+        if (it.row + it.tok_count > c.n_rows) return FAIRKV_EINVAL;      // the kernel reads exactly these rows of K and V
         if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
         if (it.part < it.chunk || it.part - it.chunk + it.n_chunks > n_parts) return FAIRKV_EINVAL;
         // the rows new tokens hide from one another (the last q_len - 1 of a pair) must not reach
         // back beyond the pair's last chunk: the kernel masks inside that chunk only
         if (q_len > 1 && it.n_chunks > 1 && it.chunk == it.n_chunks - 1 && it.tok_count < q_len - 1) return FAIRKV_EINVAL;
+        count[it.part - it.chunk] += 1 << 8;                 // pieces of the pair that starts at this slot
+        count[it.part] += 1;                                 // uses of this slot
+        if ((count[it.part] & 0xff) > 1 || (count[it.part - it.chunk] >> 8) > it.n_chunks) return FAIRKV_EINVAL;
     }
-    if (!(scale == scale) || std::isinf(scale)) return FAIRKV_EINVAL;
+    for (int32_t i = 0; i < n_items; ++i) {
+        const fairkv_item &it = items_host[i];
+        if ((count[it.part - it.chunk] >> 8) != it.n_chunks) return FAIRKV_EINVAL;
+    }
+    if (!finite(c.scale)) return FAIRKV_EINVAL;
+    const bool on_valu = c.in_dtype == FAIRKV_BF16_VALU;     // bf16 on the vector-ALU kernel: A/B measurements
+    const int32_t in_dtype = on_valu ? FAIRKV_BF16 : c.in_dtype;
     if (in_dtype != FAIRKV_BF16 && in_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
-    if (out_dtype != FAIRKV_BF16 && out_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
+    if (c.out_dtype != FAIRKV_BF16 && c.out_dtype != FAIRKV_F32) return FAIRKV_EUNSUPPORTED;
     const int G = Hq / Hkv;
     if (D != 64 && D != 128) return FAIRKV_EUNSUPPORTED;
     if (G != 1 && G != 2 && G != 4 && G != 8) return FAIRKV_EUNSUPPORTED;
     // columns of a pair: G heads times q_len new tokens; they share the 16 columns of one MFMA tile
     const int64_t cols = static_cast<int64_t>(G) * q_len;
     if (cols != 1 && cols != 2 && cols != 4 && cols != 8 && cols != 16) return FAIRKV_EUNSUPPORTED;
-    if (q_len > 1 && (in_dtype != FAIRKV_BF16 || bf16_on_valu())) return FAIRKV_EUNSUPPORTED;
-    if (kv8 && bf16_on_valu()) return FAIRKV_EUNSUPPORTED;
-    if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(items) || !aligned16(out)) return FAIRKV_EINVAL;
+    if (q_len > 1 && (in_dtype != FAIRKV_BF16 || on_valu)) return FAIRKV_EUNSUPPORTED;
+    if ((c.kv8 || c.trace) && on_valu) return FAIRKV_EUNSUPPORTED;
+    if (c.trace && deep) return FAIRKV_EUNSUPPORTED;
+    if (!aligned16(c.k) || !aligned16(c.v) || !aligned16(c.q) || !aligned16(c.items) || !aligned16(c.out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
-    if (!workspace || workspace_bytes < need) return FAIRKV_EWORKSPACE;
-    if (!aligned16(workspace)) return FAIRKV_EINVAL;
+    if (!c.workspace || c.workspace_bytes < need) return FAIRKV_EWORKSPACE;
+    if (!aligned16(c.workspace)) return FAIRKV_EINVAL;
 
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(c.hip_stream);
+    char *ws = static_cast<char *>(c.workspace);
     DecodeArgs a;
-    a.q = q;
-    a.k = k;
-    a.v = v;
-    a.items = items;
-    for (int32_t j = 0; j <= n_slots; ++j) a.slot_ptr[j] = slot_ptr[j];
-    for (int32_t j = 0; j < n_slots; ++j) {
+    a.q = c.q;
+    a.k = c.k;
+    a.v = c.v;
+    a.items = c.items;
+    // One workgroup per slot while the slot pointer fits the kernel arguments; beyond that, consecutive slots
+    // share a workgroup (their items are consecutive in the list, and a workgroup walks a list of any length).
+    const int32_t n_wg = n_slots < FAIRKV_MAX_SLOTS ? n_slots : FAIRKV_MAX_SLOTS;
+    for (int32_t j = 0; j <= n_wg; ++j) a.slot_ptr[j] = slot_ptr[static_cast<int64_t>(j) * n_slots / n_wg];
+    for (int32_t j = 0; j < n_wg; ++j) {
         a.first_row[j] = 0;
         a.first_np[j] = 0;
-        if (slot_ptr[j] == slot_ptr[j + 1]) continue;
-        const fairkv_item &it = items_host[slot_ptr[j]];
+        if (a.slot_ptr[j] == a.slot_ptr[j + 1]) continue;
+        const fairkv_item &it = items_host[a.slot_ptr[j]];
         const int64_t pair = static_cast<int64_t>(it.b) * Hkv + it.h;
         if (it.row > static_cast<int64_t>(UINT32_MAX) || pair >= (1 << 23)) continue;   // does not fit: normal start
         a.first_row[j] = static_cast<uint32_t>(it.row);
@@ -222,39 +300,43 @@ int decode_common(const void *q, const void *k, const void *v, int64_t n_rows, c
     a.n_group_counters = B * Hkv + FAIRKV_MAX_SLOTS;
     ws += fairkv_workspace_counter_bytes(B * Hkv);
     a.part_ml = reinterpret_cast<float *>(ws);
-    ws += align256(static_cast<size_t>(n_parts) * cols * 2 * sizeof(float));
+    ws += align256(part_slots(n_parts) * cols * 2 * sizeof(float));
     a.part_o = reinterpret_cast<float *>(ws);
-    a.out = out;
-    a.lse = lse;
+    a.out = c.out;
+    a.lse = c.lse;
     a.B = B;
     a.Hq = Hq;
     a.Hkv = Hkv;
-    a.out_dtype = out_dtype;
+    a.out_dtype = c.out_dtype;
     a.n_parts = n_parts;
-    a.n_rows = n_rows;
+    a.n_rows = c.n_rows;
     a.q_len = q_len;
     a.g_shift = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : 3;
-    a.scale_log2 = scale * kLog2e * k_scale;
-    a.v_scale = v_scale;
+    a.scale_log2 = c.scale * kLog2e * c.k_scale;
+    a.v_scale = c.v_scale;
     for (int h = 0; h < kScaleHeads; ++h) {     // a scale per KV head (at most kScaleHeads of them), else all 1
-        a.k_head[h] = k_head ? k_head[h % Hkv] : 1.f;
-        a.v_head[h] = v_head ? v_head[h % Hkv] : 1.f;
+        a.k_head[h] = c.k_head ? c.k_head[h % Hkv] : 1.f;
+        a.v_head[h] = c.v_head ? c.v_head[h % Hkv] : 1.f;
     }
+    a.trace = c.trace;
 
+    const bool kv8 = c.kv8;
     hipError_t e;
-    if (in_dtype == FAIRKV_BF16 && !bf16_on_valu())
-        e = kv8 ? (D == 128 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_slots, st)
-                                    : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_slots, st))
-                            : (deep ? launch_mfma<64, true, true>(static_cast<int>(cols), a, n_slots, st)
-                                    : launch_mfma<64, false, true>(static_cast<int>(cols), a, n_slots, st)))
-            : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), a, n_slots, st)
-                               : launch_mfma<128, false, false>(static_cast<int>(cols), a, n_slots, st))
-                       : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), a, n_slots, st)
-                               : launch_mfma<64, false, false>(static_cast<int>(cols), a, n_slots, st));
+    if (c.trace)
+        e = launch_mfma_trace(static_cast<int>(cols), a, n_wg, st);
+    else if (in_dtype == FAIRKV_BF16 && !on_valu)
+        e = kv8 ? (D == 128 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_wg, st)
+                                    : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_wg, st))
+                            : (deep ? launch_mfma<64, true, true>(static_cast<int>(cols), a, n_wg, st)
+                                    : launch_mfma<64, false, true>(static_cast<int>(cols), a, n_wg, st)))
+            : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), a, n_wg, st)
+                               : launch_mfma<128, false, false>(static_cast<int>(cols), a, n_wg, st))
+                       : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), a, n_wg, st)
+                               : launch_mfma<64, false, false>(static_cast<int>(cols), a, n_wg, st));
     else if (in_dtype == FAIRKV_BF16)
-        e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_slots, st);
+        e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_wg, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_wg, st);
     else
-        e = D == 128 ? launch_valu<FAIRKV_F32, 128>(G, a, n_slots, st) : launch_valu<FAIRKV_F32, 64>(G, a, n_slots, st);
+        e = D == 128 ? launch_valu<FAIRKV_F32, 128>(G, a, n_wg, st) : launch_valu<FAIRKV_F32, 64>(G, a, n_wg, st);
     return e == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
 }
 }  // namespace

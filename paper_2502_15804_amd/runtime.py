@@ -23,7 +23,7 @@ class DecodeLayer:
     """One layer's packed ragged KV cache, its plan and its output buffers on the GPU."""
 
     def __init__(self, q, k, v, off, lens, scale, params=None, out_dtype=None, want_lse=True,
-                 workspace=None, k_scale=1.0, v_scale=1.0):
+                 workspace=None, k_scale=1.0, v_scale=1.0, bf16_on_valu=False):
         import torch
 
         dev = q.device
@@ -46,6 +46,7 @@ class DecodeLayer:
         self.plan: Plan = fairkv_plan(lens_h, off_h, self.B, self.Hkv, params)
         self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
         need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G * self.q_len, self.D)
+        self.bf16_on_valu = bf16_on_valu
         if workspace is None:
             workspace = torch.zeros(need, dtype=torch.uint8, device=dev)   # arrival counters start at zero
         elif workspace.numel() < need:
@@ -54,14 +55,15 @@ class DecodeLayer:
         self.out = torch.empty(tuple(q.shape), dtype=out_dtype or torch.float32, device=dev)
         self.lse = torch.empty(tuple(q.shape[:-1]), dtype=torch.float32, device=dev) if want_lse else None
 
-    def run(self, stream=None):
+    def run(self, stream=None, trace=None):
         if self.kv8:
             fairkv_decode_attn_kv8(self.q, self.k, self.v, self.k_scale, self.v_scale, self.items_d, self.plan.items,
                                    self.plan.slot_ptr, self.plan.n_parts, self.workspace, self.out, self.lse,
                                    self.scale, self.Hkv, stream)
             return self.out, self.lse
         fairkv_decode_attn(self.q, self.k, self.v, self.items_d, self.plan.items, self.plan.slot_ptr, self.plan.n_parts,
-                           self.workspace, self.out, self.lse, self.scale, self.Hkv, stream)
+                           self.workspace, self.out, self.lse, self.scale, self.Hkv, stream,
+                           bf16_on_valu=self.bf16_on_valu, trace=trace)
         return self.out, self.lse
 
 

@@ -190,7 +190,20 @@ def test_decode_attn_validates_before_any_launch():
     assert call(sp=np.array([0, 2], np.int32)) == F.FAIRKV_EINVAL   # slot pointer does not end at n_items
     assert call(sp=np.array([1, 1], np.int32)) == F.FAIRKV_EINVAL
     big = np.zeros(322, np.int32); big[-1] = 1
-    assert call(sp=big, n_slots=321) == F.FAIRKV_EUNSUPPORTED      # too many slots for the kernel arguments
+    assert call(sp=big, n_slots=321, ws_bytes=16) == F.FAIRKV_EWORKSPACE   # more slots than workgroups: accepted as far as
+                                                                           # the workspace check (slots then share workgroups)
+    # a cut pair must come with all its pieces, each once, in consecutive partial slots
+    two = np.zeros(2, F.ITEM_DTYPE)
+    two["tok_count"], two["n_chunks"] = 2, 2
+    two["row"], two["chunk"], two["part"] = [0, 2], [0, 1], [0, 1]
+    sp2 = np.array([0, 2], np.int32)
+    assert call(ih=two, n_items=2, sp=sp2, n_parts=2, ws_bytes=16) == F.FAIRKV_EWORKSPACE      # a whole pair in two pieces
+    half = two[:1].copy()
+    assert call(ih=half, n_parts=2) == F.FAIRKV_EINVAL                                           # its second piece is missing
+    twice = two.copy(); twice["chunk"], twice["part"] = [0, 0], [0, 0]
+    assert call(ih=twice, n_items=2, sp=sp2, n_parts=2) == F.FAIRKV_EINVAL                       # the first piece twice
+    three = np.concatenate([two, two[1:]])
+    assert call(ih=three, n_items=3, sp=np.array([0, 3], np.int32), n_parts=3) == F.FAIRKV_EINVAL   # a piece too many
     assert call(n_items=0) == F.FAIRKV_EINVAL                      # every pair has at least one item
     assert call(Hq=7, Hkv=2) == F.FAIRKV_EINVAL
     assert call(n_parts=0) == F.FAIRKV_EINVAL                      # fewer parts than items
@@ -259,3 +272,24 @@ def test_decode_attn_kv8_per_head_validates_before_any_launch():
     bad[1] = np.inf
     assert call(one, bad) == F.FAIRKV_EINVAL
     assert call(one, one) == F.FAIRKV_EWORKSPACE                             # everything else valid: the 16-byte workspace is too small
+
+
+def test_trace_entry_point_validates_before_any_launch():
+    L = F.lib()
+    fake = ctypes.c_void_p(0x1000)
+    sp = np.array([0, 1], np.int32)
+    it = np.zeros(1, F.ITEM_DTYPE)
+    it["tok_count"], it["n_chunks"] = 5, 1
+
+    def trace(tr=fake, tr_bytes=1 << 20, D=128, Hq=8, n_slots=1, ws_bytes=16):
+        spp = np.zeros(n_slots + 1, np.int32)
+        spp[-1] = 1
+        return L.fairkv_decode_attn_trace(fake, fake, fake, 5, fake, it.ctypes.data, 1, spp.ctypes.data, n_slots, 1, fake,
+                                          ws_bytes, fake, None, 1, Hq, 1, D, 0.1, tr, tr_bytes, None)
+
+    assert trace(tr=None) == F.FAIRKV_EINVAL
+    assert trace(tr_bytes=64) == F.FAIRKV_EINVAL                 # room for half a workgroup's stamps
+    assert trace(D=64) == F.FAIRKV_EUNSUPPORTED
+    assert trace(Hq=2) == F.FAIRKV_EUNSUPPORTED
+    assert trace(n_slots=321) == F.FAIRKV_EUNSUPPORTED
+    assert trace() == F.FAIRKV_EWORKSPACE                        # everything else valid: the 16-byte workspace is too small

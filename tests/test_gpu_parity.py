@@ -29,14 +29,15 @@ def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison
     F = _F()
     p = F.fairkv_default_params(256, policy=policy, n_slots=n_slots, **params)
     layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype)
-    for _ in range(calls):      # a second call checks that the first left the arrival counters at zero
+    for _ in range(calls):      # a second call finds the workspace as the first left it
+        counters = F.fairkv_workspace_counter_bytes(lens.size)              # the first region of the workspace
         if poison:
             layer.out.fill_(float("nan"))
             layer.lse.fill_(float("nan"))
-            counters = F.fairkv_workspace_counter_bytes(lens.size)          # the first region of the workspace
-            layer.workspace[counters:].fill_(0xFF)
+            layer.workspace[counters:].fill_(0xFF)                          # nothing but the counters carries state
         layer.run()
         torch.cuda.synchronize()
+        assert int(layer.workspace[:counters].count_nonzero().item()) == 0   # every completed call leaves them zero
     return layer.out.float().cpu().numpy().astype(np.float64), layer.lse.cpu().numpy().astype(np.float64), layer
 
 
@@ -350,8 +351,7 @@ def test_pairs_cut_into_very_many_pieces_are_merged_in_two_levels():
         w, off, q, k, v = make_case(B, Hkv * G, Hkv, 128, "bf16", lens, seed=int(rng.integers(1 << 20)), gap_rows=1)
         err, layer = check(w, q, k, v, off, lens, policy=3, n_slots=n_slots, min_chunk=32, overhead_tokens=16, calls=3)
         assert layer.plan.items["n_chunks"].max() >= 32
-        nb = F.fairkv_workspace_counter_bytes(B * Hkv)
-        assert int(layer.workspace[:nb].view(torch.int32).abs().sum().item()) == 0
+        assert int(layer.workspace[:F.fairkv_workspace_counter_bytes(B * Hkv)].count_nonzero().item()) == 0
     # equal shares with a tiny cap on the counter index: the pair falls back to one level
     lens = np.array([[5000, 5000, 5000]], np.int32)
     w, off, q, k, v = make_case(1, 6, 3, 64, "bf16", lens, seed=5)
@@ -381,9 +381,11 @@ def _kv8_check(w, off, lens, q, k8, v8, k_scale, v_scale, out_dtype=None, **para
     for _ in range(2):
         layer.out.fill_(float("nan"))
         layer.lse.fill_(float("nan"))
-        layer.workspace[F.fairkv_workspace_counter_bytes(lens.size):].fill_(0xFF)
+        counters = F.fairkv_workspace_counter_bytes(lens.size)
+        layer.workspace[counters:].fill_(0xFF)
         layer.run()
         torch.cuda.synchronize()
+        assert int(layer.workspace[:counters].count_nonzero().item()) == 0
     out = layer.out.float().cpu().numpy().astype(np.float64)
     lse = layer.lse.cpu().numpy().astype(np.float64)
     assert out.shape == ro.shape and np.isfinite(out).all()

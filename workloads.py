@@ -85,16 +85,16 @@ class Workload:
 
 WORKLOADS = {
     "tiny": Workload("tiny", 2, 8, 4, 64, "f32", 1, 1e-5,
-                     "B=2, 4 KV heads x 2 query heads, D=64, fp32; len uniform in [1,128]"),
+                     "B=2, 4 KV heads x 2 query heads, D=64, fp32; len uniform in 1..128"),
     "llama70b": Workload("llama70b", 16, 64, 8, 128, "bf16", 32, 1e-2,
                          "Llama-70B-shaped layer: 64 q / 8 KV heads, D=128, bf16, B=16; "
-                         "lognormal budgets mean 1024, sigma 0.6, clip [16,8192]"),
+                         "lognormal budgets mean 1024, sigma 0.6, clip 16..8192"),
     "mistral24b": Workload("mistral24b", 32, 32, 8, 128, "bf16", 8, 1e-2,
                            "Mistral-24B-shaped layer: 32 q / 8 KV heads, D=128, bf16, B=32; "
-                           "KV heads 2 and 5 heavy (mean 4096), others mean 512, clip [16,16384]"),
+                           "KV heads 2 and 5 heavy (mean 4096), others mean 512, clip 16..16384"),
     "faircopy": Workload("faircopy", 64, 16, 2, 128, "bf16", 8, 1e-2,
                          "one GPU's Fair-Copying share: full head (B=64, mean 2048) + replicated "
-                         "heavy head serving rows 32-63 only (mean 6144), clip [16,32768]"),
+                         "heavy head serving rows 32-63 only (mean 6144), clip 16..32768"),
     "stress": Workload("stress", 128, 64, 8, 128, "bf16", 80, 1e-2,
                        "Llama-70B shape, B=128, 80 layers; Pareto(alpha 1.2, min 32) clip 32768"),
 }
