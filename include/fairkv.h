@@ -309,6 +309,25 @@ int fairkv_decode_attn_kv8_per_head(const void *q, const void *k8, const void *v
                                     int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D,
                                     int32_t out_dtype, float scale, void *hip_stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  fairkv_decode_attn_multi with the workspace inside the library: a device
+ * array of FAIRKV_STATIC_WORKSPACE_BYTES that is part of the loaded library on every GPU (each GPU the library
+ * runs on holds it until the process ends).  The call allocates and frees nothing, on the device or on the
+ * host; inputs and outputs are the caller's as before.
+ * Returns FAIRKV_EWORKSPACE when fairkv_workspace_bytes(n_parts, B*Hkv, G*q_len, D) exceeds
+ * FAIRKV_STATIC_WORKSPACE_BYTES (8 MiB: about 1500 partial slots at G = 8, D = 128; the largest workload here,
+ * 1024 pairs on 256 slots, needs 1279).  Everything else as fairkv_decode_attn_multi, same kernels.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * different host threads without ordering) race; order them on one stream.  The array is zero when the
+ * library is loaded; a call needs only the arrival counters at the array's start to be zero, and every
+ * completed call leaves them zero, whatever its sizes (nothing else is read before it is written). */
+enum { FAIRKV_STATIC_WORKSPACE_BYTES = 8 << 20 };
+int fairkv_decode_attn_static(const void *q, const void *k, const void *v, int64_t n_rows,
+                              const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                              const int32_t *slot_ptr, int32_t n_slots, int32_t n_parts, void *out, float *lse,
+                              int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D,
+                              int32_t in_dtype, int32_t out_dtype, float scale, void *hip_stream);
+
 /* ---- building and growing the packed cache (the step before the path) ---------------------------
  *
  * fairkv_pack gathers the tokens a per-head compressor kept (Section 2: which entries a method

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfairkv.so")
 FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, FAIRKV_EHIP = 0, -1, -2, -3, -4, -5
 FAIRKV_BF16, FAIRKV_F32, FAIRKV_E4M3, FAIRKV_BF16_VALU = 0, 1, 2, 3
 FAIRKV_TRACE_STAMPS = 16
+FAIRKV_STATIC_WORKSPACE_BYTES = 8 << 20
 FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
 FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
@@ -26,7 +27,7 @@ FAIRKV_PLACE_AUTO, FAIRKV_PLACE_EXACT, FAIRKV_PLACE_GREEDY = 0, 1, 2
 EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fairkv_workspace_counter_bytes",
            "fairkv_decode_attn",
            "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8", "fairkv_decode_attn_kv8_per_head",
-           "fairkv_decode_attn_trace",
+           "fairkv_decode_attn_static", "fairkv_decode_attn_trace",
            "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
 
 
@@ -119,6 +120,9 @@ def lib() -> ctypes.CDLL:
         L.fairkv_decode_attn_kv8_per_head.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, vp, vp, i32, vp,
                                                       i32, i32, vp, ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32,
                                                       ctypes.c_float, vp]
+        L.fairkv_decode_attn_static.restype = ctypes.c_int
+        L.fairkv_decode_attn_static.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp, vp,
+                                                i32, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.fairkv_decode_attn_trace.restype = ctypes.c_int
         L.fairkv_decode_attn_trace.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp, ctypes.c_size_t,
                                                vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -238,8 +242,8 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
                        bf16_on_valu=False, trace=None):
     """Enqueue decode attention for one layer on `stream` (default: torch's current stream).
 
-    trace (a zero-filled int64 device tensor of n_slots * FAIRKV_TRACE_STAMPS) calls fairkv_decode_attn_trace;
-    bf16_on_valu passes FAIRKV_BF16_VALU.
+    workspace=None calls fairkv_decode_attn_static (the library's own workspace); trace (a zero-filled int64 device
+    tensor of n_slots * FAIRKV_TRACE_STAMPS) calls fairkv_decode_attn_trace; bf16_on_valu passes FAIRKV_BF16_VALU.
 
     Tensor arguments are CUDA/HIP torch tensors owned by the caller: q [B,Hq,D], or [B,q_len,Hq,D] for
     several new tokens per sequence (fairkv_decode_attn_multi; out and lse then carry q_len too); k, v [rows,D];
@@ -284,11 +288,15 @@ def fairkv_decode_attn(q, k, v, items, items_host, slot_ptr, n_parts, workspace,
             slot_ptr.ctypes.data, slot_ptr.size - 1, int(n_parts))
     st = ctypes.c_void_p(stream.cuda_stream)
     if trace is not None:
-        if q_len != 1 or trace.dtype != torch.int64:
-            raise ValueError("a traced call is a single-token call with an int64 trace buffer")
+        if q_len != 1 or workspace is None or trace.dtype != torch.int64:
+            raise ValueError("a traced call is a single-token call with a caller's workspace and an int64 trace buffer")
         name = "fairkv_decode_attn_trace"
         rc = lib().fairkv_decode_attn_trace(*head, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out),
                                             _ptr(lse), B, Hq, Hkv, D, float(scale), _ptr(trace), trace.numel() * 8, st)
+    elif workspace is None:
+        name = "fairkv_decode_attn_static"
+        rc = lib().fairkv_decode_attn_static(*head, _ptr(out), _ptr(lse), B, q_len, Hq, Hkv, D, in_dt, dt[out.dtype],
+                                             float(scale), st)
     else:
         name = "fairkv_decode_attn_multi" if q_len > 1 else "fairkv_decode_attn"
         rc = lib().fairkv_decode_attn_multi(*head, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out),

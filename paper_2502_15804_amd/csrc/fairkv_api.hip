@@ -9,6 +9,7 @@
 // Section 4.2); the workgroup that delivers the last partial result of a pair combines them.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -121,6 +122,8 @@ struct DecodeCall {
     float k_scale = 1.f, v_scale = 1.f;
     const float *k_head = nullptr, *v_head = nullptr;
     unsigned long long *trace = nullptr;
+    int32_t *count_scratch = nullptr;      // host, n_parts ints, for callers that must not allocate; else a vector is used
+    bool static_workspace = false;         // the library's own array instead of `workspace`
     void *hip_stream;
 };
 
@@ -216,6 +219,54 @@ extern "C" int fairkv_decode_attn_trace(const void *q, const void *k, const void
     return decode_common(c);
 }
 
+// ---- the entry point that allocates nothing ------------------------------------------------------
+namespace {
+
+// The workspace of fairkv_decode_attn_static: one array per GPU, part of the loaded code object and zero when
+// that is loaded.  Only the arrival counters at its start need to be zero for a call, and every completed call
+// leaves them zero, whatever its sizes (the counter region starts at offset 0 for every B * Hkv).
+static __device__ __align__(256) unsigned char scratch[FAIRKV_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+constexpr int32_t kStaticMaxParts = FAIRKV_STATIC_WORKSPACE_BYTES / 256;   // a partial slot is at least 264 bytes
+
+// Address of `scratch` on every device, looked up once per device with that device current.  In host code the
+// array's name is only a handle for this lookup: the address it yields is what kernels and copies are given.
+void *scratch_of_current_device()
+{
+    static std::atomic<void *> ptr[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    ptr[dev].store(p, std::memory_order_release);       // every thread that looks it up finds the same address
+    return p;
+}
+
+}  // namespace
+
+extern "C" int fairkv_decode_attn_static(const void *q, const void *k, const void *v, int64_t n_rows,
+                                         const fairkv_item *items, const fairkv_item *items_host, int32_t n_items,
+                                         const int32_t *slot_ptr, int32_t n_slots, int32_t n_parts, void *out, float *lse,
+                                         int32_t B, int32_t q_len, int32_t Hq, int32_t Hkv, int32_t D, int32_t in_dtype,
+                                         int32_t out_dtype, float scale, void *hip_stream)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || q_len < 1 || n_parts < 0 || Hq % Hkv != 0) return FAIRKV_EINVAL;
+    const int64_t cols = static_cast<int64_t>(Hq / Hkv) * q_len;
+    if (static_cast<int64_t>(B) * Hkv > INT32_MAX || cols > 16 || D > 128) return FAIRKV_EUNSUPPORTED;
+    if (n_parts > kStaticMaxParts ||
+        fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D) > FAIRKV_STATIC_WORKSPACE_BYTES)
+        return FAIRKV_EWORKSPACE;       // this plan needs more than the built-in workspace holds
+    static thread_local int32_t count_scratch[kStaticMaxParts];      // host side of the plan check, no heap
+    DecodeCall c = make_call(q, k, v, n_rows, items, items_host, n_items, slot_ptr, n_slots, n_parts, nullptr,
+                             FAIRKV_STATIC_WORKSPACE_BYTES, out, lse, B, q_len, Hq, Hkv, D, in_dtype, out_dtype, scale,
+                             hip_stream);
+    c.count_scratch = count_scratch;
+    c.static_workspace = true;          // looked up after every check that needs no device has passed
+    return decode_common(c);
+}
+
 namespace {
 int decode_common(const DecodeCall &c)
 {
@@ -234,7 +285,14 @@ int decode_common(const DecodeCall &c)
     // pair's arrival counter short for ever (no output, and a counter that is not zero for the next call); one
     // that comes twice would have two workgroups write one partial slot.  count[first slot of a pair] counts
     // that pair's pieces; a piece's own slot must be used once.
-    std::vector<int32_t> count(static_cast<size_t>(n_parts), 0);
+    std::vector<int32_t> count_own;
+    int32_t *count = c.count_scratch;
+    if (!count) {
+        count_own.assign(static_cast<size_t>(n_parts), 0);
+        count = count_own.data();
+    } else {
+        for (int32_t i = 0; i < n_parts; ++i) count[i] = 0;
+    }
     bool deep = false;      // a pair in very many pieces: the kernel with the two-level merge
     for (int32_t i = 0; i < n_items; ++i) {
         const fairkv_item &it = items_host[i];
@@ -271,11 +329,12 @@ int decode_common(const DecodeCall &c)
     if (!aligned16(c.k) || !aligned16(c.v) || !aligned16(c.q) || !aligned16(c.items) || !aligned16(c.out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
-    if (!c.workspace || c.workspace_bytes < need) return FAIRKV_EWORKSPACE;
-    if (!aligned16(c.workspace)) return FAIRKV_EINVAL;
+    if (c.workspace_bytes < need || (!c.static_workspace && !c.workspace)) return FAIRKV_EWORKSPACE;
+    if (!c.static_workspace && !aligned16(c.workspace)) return FAIRKV_EINVAL;
 
     hipStream_t st = static_cast<hipStream_t>(c.hip_stream);
-    char *ws = static_cast<char *>(c.workspace);
+    char *ws = static_cast<char *>(c.static_workspace ? scratch_of_current_device() : c.workspace);
+    if (!ws) return FAIRKV_EHIP;
     DecodeArgs a;
     a.q = c.q;
     a.k = c.k;

@@ -23,7 +23,7 @@ class DecodeLayer:
     """One layer's packed ragged KV cache, its plan and its output buffers on the GPU."""
 
     def __init__(self, q, k, v, off, lens, scale, params=None, out_dtype=None, want_lse=True,
-                 workspace=None, k_scale=1.0, v_scale=1.0, bf16_on_valu=False):
+                 workspace=None, k_scale=1.0, v_scale=1.0, static_workspace=False, bf16_on_valu=False):
         import torch
 
         dev = q.device
@@ -47,7 +47,9 @@ class DecodeLayer:
         self.items_d = torch.from_numpy(self.plan.items.view(np.uint8).copy()).to(dev)
         need = fairkv_workspace_bytes(self.plan.n_parts, self.B * self.Hkv, self.G * self.q_len, self.D)
         self.bf16_on_valu = bf16_on_valu
-        if workspace is None:
+        if static_workspace:
+            workspace = None                                               # the library's own (fairkv_decode_attn_static)
+        elif workspace is None:
             workspace = torch.zeros(need, dtype=torch.uint8, device=dev)   # arrival counters start at zero
         elif workspace.numel() < need:
             raise ValueError("shared workspace too small for this layer")

@@ -274,12 +274,27 @@ def test_decode_attn_kv8_per_head_validates_before_any_launch():
     assert call(one, one) == F.FAIRKV_EWORKSPACE                             # everything else valid: the 16-byte workspace is too small
 
 
-def test_trace_entry_point_validates_before_any_launch():
+def test_static_and_trace_entry_points_validate_before_any_launch():
     L = F.lib()
     fake = ctypes.c_void_p(0x1000)
     sp = np.array([0, 1], np.int32)
     it = np.zeros(1, F.ITEM_DTYPE)
     it["tok_count"], it["n_chunks"] = 5, 1
+
+    def static(n_parts=1, B=1, Hq=8, Hkv=1, q_len=1, D=128, q=fake, n_rows=5):
+        return L.fairkv_decode_attn_static(q, fake, fake, n_rows, fake, it.ctypes.data, 1, sp.ctypes.data, 1, n_parts, fake,
+                                           None, B, q_len, Hq, Hkv, D, 0, 1, 0.1, None)
+
+    # the built-in workspace has a stated size: plans that need more are refused, whatever else they are
+    assert F.fairkv_workspace_bytes(1500, 128, 8, 128) <= F.FAIRKV_STATIC_WORKSPACE_BYTES
+    assert static(n_parts=4000) == F.FAIRKV_EWORKSPACE
+    assert static(n_parts=(8 << 20) // 256 + 1) == F.FAIRKV_EWORKSPACE
+    assert static(n_parts=1000, B=1 << 20, Hkv=1, Hq=8) == F.FAIRKV_EWORKSPACE       # the counters alone fill it
+    assert static(q=None) == F.FAIRKV_EINVAL
+    assert static(n_rows=4) == F.FAIRKV_EINVAL
+    assert static(Hq=7, Hkv=2) == F.FAIRKV_EINVAL
+    assert static(D=96) == F.FAIRKV_EUNSUPPORTED
+    assert static(q_len=3) == F.FAIRKV_EUNSUPPORTED
 
     def trace(tr=fake, tr_bytes=1 << 20, D=128, Hq=8, n_slots=1, ws_bytes=16):
         spp = np.zeros(n_slots + 1, np.int32)
