@@ -61,6 +61,8 @@ def parse():
     ap.add_argument("--phases", action="store_true",
                     help="instead of the benchmark: one traced launch per layer (fairkv_decode_attn_trace) after a "
                          "warm rotation; prints where the time of a launch goes, per phase, from the GPU's wall clock")
+    ap.add_argument("--phases-raw", default=None, metavar="FILE.npz",
+                    help="with --phases: also save the stamps of every workgroup and what its slot held")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -583,7 +585,7 @@ def phases(a, overrides):
              "last item streamed (wave 0)", "hand-over begins", "partials' stores issued", "counted in", "merged",
              "hand-over ends", "end"]
     per_layer = []
-    rows = {k: [] for k in ("has_handover", "merges", "n_items", "tokens")}
+    rows = {k: [] for k in ("has_handover", "merges", "n_items", "tokens", "n_cut", "n_solo", "n_whole")}
     for li, layer in enumerate(rot.layers):
         trace = torch.zeros(n_slots * S, dtype=torch.int64, device="cuda")
         rot.layers[li - 1].run()                      # keeps the pipeline as in a running rotation
@@ -598,6 +600,12 @@ def phases(a, overrides):
         cnt = np.diff(pl.slot_ptr)
         rows["n_items"].append(cnt)
         rows["tokens"].append(np.array([pl.items["tok_count"][pl.slot_ptr[j]:pl.slot_ptr[j + 1]].sum() for j in range(n_slots)]))
+        it = pl.items
+        solo_max = 96                                            # whole pairs up to this many tokens run on one wave
+        for key, mask in (("n_cut", it["n_chunks"] > 1), ("n_solo", (it["n_chunks"] == 1) & (it["tok_count"] <= solo_max)),
+                          ("n_whole", (it["n_chunks"] == 1) & (it["tok_count"] > solo_max))):
+            csum = np.concatenate([[0], np.cumsum(mask.astype(np.int64))])
+            rows[key].append(csum[pl.slot_ptr[1:]] - csum[pl.slot_ptr[:-1]])
         rows["has_handover"].append(~np.isnan(us[:, 6]))
         rows["merges"].append((us[:, 9] - us[:, 8]) > 0.15)
     us = np.stack(per_layer)                                      # [layers, slots, stamps]
@@ -628,6 +636,31 @@ def phases(a, overrides):
            }
     n_items = np.concatenate(rows["n_items"])
     dur = np.concatenate([u[:, 11] - u[:, 0] for u in per_layer])
+    # least squares: what a token and an item of each kind cost a slot (the planner's cost model, Section 3.2's
+    # L = gamma C + delta at the level of one workgroup); the streaming part alone, and up to the end
+    feats = np.stack([np.ones_like(dur), np.concatenate(rows["tokens"]).astype(float), np.concatenate(rows["n_cut"]).astype(float),
+                      np.concatenate(rows["n_whole"]).astype(float), np.concatenate(rows["n_solo"]).astype(float)], axis=1)
+    ok_rows = ~np.isnan(dur)
+    fit = {}
+    for label, y in (("until_end", dur), ("until_last_item_streamed", np.concatenate([u[:, 5] - u[:, 0] for u in per_layer]))):
+        m = ok_rows & ~np.isnan(y)
+        use = [j for j in range(feats.shape[1]) if feats[m, j].std() > 0 or j == 0]
+        coef, *_ = np.linalg.lstsq(feats[m][:, use], y[m], rcond=None)
+        full = dict(zip([["fixed_us", "us_per_token", "us_per_cut_piece", "us_per_whole_pair", "us_per_short_pair"][j] for j in use],
+                        [round(float(c), 4) for c in coef]))
+        if full.get("us_per_token", 0) > 0:
+            for k_ in list(full):
+                if k_.startswith("us_per_") and k_ != "us_per_token":
+                    full[k_.replace("us_per_", "tokens_per_")] = round(full[k_] / full["us_per_token"], 1)
+        resid = y[m] - feats[m][:, use] @ coef
+        full["residual_rms_us"] = round(float(np.sqrt((resid ** 2).mean())), 3)
+        fit[label] = full
+    rec["slot_time_model"] = fit
+    if a.phases_raw:
+        np.savez_compressed(a.phases_raw, us=us, tokens=np.stack(rows["tokens"]), n_cut=np.stack(rows["n_cut"]),
+                            n_whole=np.stack(rows["n_whole"]), n_solo=np.stack(rows["n_solo"]), merges=np.stack(rows["merges"]),
+                            max_chunks=np.stack([np.array([l.plan.items["n_chunks"][l.plan.slot_ptr[j]:l.plan.slot_ptr[j + 1]].max(initial=0)
+                                                           for j in range(n_slots)]) for l in rot.layers]))
     rec["by_items_in_slot"] = {str(int(k)): {"slots": int((n_items == k).sum()), "median_us": round(q(dur[n_items == k], 50), 2),
                                              "median_tokens": int(np.median(np.concatenate(rows["tokens"])[n_items == k]))}
                                for k in np.unique(n_items) if (n_items == k).sum() >= 8}

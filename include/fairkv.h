@@ -52,6 +52,9 @@ enum { FAIRKV_BF16 = 0, FAIRKV_F32 = 1,
        FAIRKV_E4M3 = 2, /* one byte per element: fairkv_pack and fairkv_append only (they move bytes) */
        FAIRKV_BF16_VALU = 3 /* in_dtype of fairkv_decode_attn only: bf16 inputs through the vector-ALU kernel that
                                serves fp32 instead of the matrix-core kernel; for A/B measurements of the two */ };
+enum { FAIRKV_SHORT_PAIR_TOKENS = 96 }; /* a whole pair of at most this many tokens is a "short pair": the bf16 and 8-bit
+                                           kernels let one wave run it alone (four such pairs stream side by side,
+                                           no fold across waves), and the planner may charge it its own overhead */
 enum { FAIRKV_MAX_SLOTS = 320 };   /* most workgroups fairkv_decode_attn launches; a plan with more slots is run with
                                       consecutive slots sharing a workgroup */
 
@@ -92,7 +95,8 @@ typedef struct {
     int32_t overhead_tokens; /* fixed cost of an item in token units: the offset of the
                                 linear latency model of Section 3.2 (>= 0) */
     int32_t policy;          /* FAIRKV_POLICY_* */
-    int32_t reserved;        /* must be 0 */
+    int32_t short_overhead_tokens; /* the same for an item that is a short pair (a whole pair of at most
+                                FAIRKV_SHORT_PAIR_TOKENS tokens, empty pairs included); 0: overhead_tokens (>= 0) */
 } fairkv_plan_params;
 
 typedef struct {
@@ -105,16 +109,18 @@ typedef struct {
 
 /* Defaults: n_slots = n_compute_units, tile 16, min_chunk 32, max_split 256, oversub 2,
  * overhead_tokens 128 (measured on MI355X: an extra item in a slot costs about as much as
- * streaming 100-150 tokens), policy FAIR.  n_compute_units must be >= 1. */
+ * streaming 100-150 tokens), short_overhead_tokens 48 (a short pair costs a slot about a third
+ * of that), policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
 /*
  * Host-side planner (integer arithmetic only; deterministic).  An item costs
- * tok_count + overhead_tokens; the load of a slot is the sum over its items (objective: eq. 4).
+ * tok_count + ov, ov = short_overhead_tokens for a short pair (if that is not 0) and overhead_tokens
+ * otherwise; the load of a slot is the sum over its items (objective: eq. 4).
  *
  * FAIR       pairs in (b, h) order fill slot 0, 1, ...  A slot opened as number j gets the budget
- *            ceil((tokens not yet placed + overhead * (pairs unfinished + slots unopened)) /
- *            slots unopened).  With fit = the whole tiles that still fit the slot's room: a pair
+ *            ceil((tokens not yet placed + the ov of every pair not yet finished, taken whole +
+ *            overhead_tokens * slots unopened) / slots unopened).  With fit = the whole tiles that still fit the slot's room: a pair
  *            (or its rest) that fits is placed whole; else it is cut at `fit` if both pieces are
  *            >= min_chunk; else it is placed whole anyway if the excess is <= fit; else the slot
  *            is closed and the next one opened.  After a cut the rest goes on in the next slot.
@@ -365,8 +371,8 @@ int fairkv_append(const void *k_new, const void *v_new, int32_t B, int32_t Hkv, 
  * and step; re-plan with fairkv_plan every few hundred steps. */
 int fairkv_plan_grow(fairkv_item *items, int32_t n_items, int32_t B, int32_t Hkv, int32_t *len, const int32_t *cap);
 
-/* Measurement aid, not part of the method: fairkv_decode_attn (bf16 in, fp32 out, D = 128, G = 4 or 8, plans
- * without a pair in 32 pieces or more; else FAIRKV_EUNSUPPORTED) through an instantiation of the same kernel
+/* Measurement aid, not part of the method: fairkv_decode_attn (bf16 in, fp32 out, D = 128, G = 4 or 8; else
+ * FAIRKV_EUNSUPPORTED) through an instantiation of the same kernel
  * that also stamps the phases of every workgroup with the GPU's 100 MHz wall clock.
  * trace: device, FAIRKV_TRACE_STAMPS uint64 per workgroup (trace_bytes >= n_slots * FAIRKV_TRACE_STAMPS * 8, else
  * FAIRKV_EINVAL), zero-filled by the caller; stamp k of workgroup j is trace[j * FAIRKV_TRACE_STAMPS + k]:

@@ -26,7 +26,8 @@ without search.  Four policies, mirroring the paper's ablation (Section 5.2.1):
              up to one tile and the per-item overhead.
 
 An item costs tok_count + overhead_tokens (the linear latency model with an
-offset of Section 3.2).  Pairs with no tokens still get one empty item, so that
+offset of Section 3.2); a short pair (a whole pair of at most SHORT_PAIR_TOKENS
+tokens) may be given a fixed cost of its own, short_overhead_tokens.  Pairs with no tokens still get one empty item, so that
 some slot writes their zero output.  Several plans can be equally good in the
 paper's sense; order and tie-breaks are fixed only so that two implementations
 can be compared field by field.  All arithmetic is on Python ints.
@@ -51,6 +52,10 @@ class Params:
     oversub: int = 2
     overhead_tokens: int = 128
     policy: int = POLICY_FAIR
+    short_overhead_tokens: int = 0    # fixed cost of a short pair (a whole pair of at most SHORT_PAIR_TOKENS); 0: overhead_tokens
+
+
+SHORT_PAIR_TOKENS = 96
 
 
 @dataclass(frozen=True)
@@ -93,8 +98,8 @@ def validate(B: int, Hkv: int, lens, offs, p: Params) -> None:
         raise ValueError("n_slots, tile, max_split, oversub must be >= 1")
     if p.min_chunk < p.tile or p.min_chunk % p.tile != 0:
         raise ValueError("min_chunk must be a positive multiple of tile")
-    if p.overhead_tokens < 0:
-        raise ValueError("overhead_tokens must be >= 0")
+    if p.overhead_tokens < 0 or p.short_overhead_tokens < 0:
+        raise ValueError("overhead_tokens and short_overhead_tokens must be >= 0")
     if p.policy not in (POLICY_NAIVE, POLICY_LPT, POLICY_LPT_SPLIT, POLICY_FAIR):
         raise ValueError("unknown policy")
 
@@ -115,6 +120,12 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
     total = sum(lens)
     S, ov = p.n_slots, p.overhead_tokens
 
+    def item_ov(count: int, whole_pair: bool) -> int:
+        """Fixed cost of an item: a short pair taken whole has its own (the kernel runs it on one wave)."""
+        if whole_pair and count <= SHORT_PAIR_TOKENS and p.short_overhead_tokens > 0:
+            return p.short_overhead_tokens
+        return ov
+
     def up(x: int) -> int:
         return _ceil_div(x, p.tile) * p.tile
 
@@ -131,28 +142,31 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
         # min_chunk is made: the slot is overfilled with the whole rest of the pair if that
         # excess is smaller than the room it would otherwise leave unused, else it is closed.
         # The last slot takes whatever is left.
-        tokens_left, pairs_left = total, n_pairs
+        tokens_left = total
+        ov_left = sum(item_ov(n, True) for n in lens)       # fixed costs of the unfinished pairs, each taken whole
 
         def budget_for(j: int) -> int:
             open_slots = S - j
-            return _ceil_div(tokens_left + ov * (pairs_left + open_slots), open_slots)
+            return _ceil_div(tokens_left + ov_left + ov * open_slots, open_slots)
 
         j = 0
         room = budget_for(0)
         for pair in range(n_pairs):
             left, begin, c = lens[pair], 0, 0
             if left == 0:
-                if room < ov and j < S - 1:
+                if room < item_ov(0, True) and j < S - 1:
                     j += 1
                     room = budget_for(j)
                 slots[j].append((pair, 0, 0, 0))
-                room -= ov
+                room -= item_ov(0, True)
                 c = 1
             while left > 0:
                 last_slot = j == S - 1
                 last_copy = c == p.max_split - 1            # eq. 3: no further copy allowed
-                fit = max(0, (room - ov) // p.tile * p.tile)  # whole tiles that still fit here
-                if last_slot or last_copy or left <= fit:
+                ov_take_all = item_ov(left, begin == 0)      # if this item takes all that is left of the pair
+                fit_all = max(0, (room - ov_take_all) // p.tile * p.tile)
+                fit = max(0, (room - ov) // p.tile * p.tile)  # whole tiles that still fit here (a piece of a cut pair)
+                if last_slot or last_copy or left <= fit_all:
                     take = left
                 elif fit >= p.min_chunk and left - fit >= p.min_chunk:
                     take = fit                               # cut: neither piece is tiny
@@ -163,14 +177,14 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
                     room = budget_for(j)
                     continue
                 slots[j].append((pair, begin, take, c))
-                room -= take + ov
+                room -= take + (ov_take_all if take == left else ov)
                 begin, left, c = begin + take, left - take, c + 1
                 tokens_left -= take
                 if left > 0 and j < S - 1:                   # slot is full: go on in the next
                     j += 1
                     room = budget_for(j)
             n_chunks_of[pair] = c
-            pairs_left -= 1
+            ov_left -= item_ov(lens[pair], True)
     else:
         if p.policy == POLICY_LPT_SPLIT:
             target = max(p.min_chunk, up(_ceil_div(total, S * p.oversub)))
@@ -196,7 +210,7 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
             load = [0] * S
             for pc in sorted(pieces, key=lambda x: (-x[2], x[0], x[3])):
                 j = min(range(S), key=lambda s: (load[s], s))
-                load[j] += pc[2] + ov
+                load[j] += pc[2] + item_ov(pc[2], n_chunks_of[pc[0]] == 1)
                 slots[j].append(pc)
 
     part_base = [0] * (n_pairs + 1)
@@ -211,7 +225,7 @@ def plan(lens, offs, B: int, Hkv: int, p: Params):
             b, h = divmod(pair, Hkv)
             items.append(Item(offs[pair] + begin, count, b, h, c, n_chunks_of[pair], part_base[pair] + c))
         slot_ptr[j + 1] = len(items)
-        loads.append(sum(pc[2] + ov for pc in slots[j]))
+        loads.append(sum(pc[2] + item_ov(pc[2], n_chunks_of[pc[0]] == 1) for pc in slots[j]))
 
     summary = Summary(total, max(loads), min(loads), len(items), part_base[n_pairs])
     return items, slot_ptr, part_base, summary
@@ -231,9 +245,11 @@ def grow(items, lens, cap, Hkv: int):
 
 
 # ---- figures of merit, straight from the paper's definitions ------------------------
-def slot_loads(items, slot_ptr, overhead_tokens: int):
-    return [sum(it.tok_count + overhead_tokens for it in items[slot_ptr[j]:slot_ptr[j + 1]])
-            for j in range(len(slot_ptr) - 1)]
+def slot_loads(items, slot_ptr, overhead_tokens: int, short_overhead_tokens: int = 0):
+    def cost(it):
+        short = it.n_chunks == 1 and it.tok_count <= SHORT_PAIR_TOKENS and short_overhead_tokens > 0
+        return it.tok_count + (short_overhead_tokens if short else overhead_tokens)
+    return [sum(cost(it) for it in items[slot_ptr[j]:slot_ptr[j + 1]]) for j in range(len(slot_ptr) - 1)]
 
 
 def delta(loads) -> int:

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfairkv.so")
 FAIRKV_OK, FAIRKV_EINVAL, FAIRKV_ECAP, FAIRKV_EWORKSPACE, FAIRKV_EUNSUPPORTED, FAIRKV_EHIP = 0, -1, -2, -3, -4, -5
 FAIRKV_BF16, FAIRKV_F32, FAIRKV_E4M3, FAIRKV_BF16_VALU = 0, 1, 2, 3
 FAIRKV_TRACE_STAMPS = 16
+FAIRKV_SHORT_PAIR_TOKENS = 96
 FAIRKV_STATIC_WORKSPACE_BYTES = 8 << 20
 FAIRKV_POLICY_NAIVE, FAIRKV_POLICY_LPT, FAIRKV_POLICY_LPT_SPLIT, FAIRKV_POLICY_FAIR = 0, 1, 2, 3
 
@@ -38,7 +39,7 @@ class fairkv_item(ctypes.Structure):
 
 class fairkv_plan_params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens", "policy", "reserved")]
+                ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens", "policy", "short_overhead_tokens")]
 
 
 class fairkv_plan_summary(ctypes.Structure):
@@ -83,6 +84,12 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with "
                               f"`python -m paper_2502_15804_amd.build` (there is no fallback path)")
+        try:
+            # PyTorch ships a HIP runtime of its own: load it first, so that this library binds to the same one
+            # (two runtimes in one process do not share streams or code objects, and every launch would fail)
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
         L.fairkv_default_params.restype = ctypes.c_int
@@ -175,7 +182,10 @@ class Plan:
         return int(self.params.n_slots)
 
     def slot_loads(self) -> np.ndarray:
-        cost = self.items["tok_count"].astype(np.int64) + int(self.params.overhead_tokens)
+        short = ((self.items["n_chunks"] == 1) & (self.items["tok_count"] <= FAIRKV_SHORT_PAIR_TOKENS)
+                 & (int(self.params.short_overhead_tokens) > 0))
+        cost = self.items["tok_count"].astype(np.int64) + np.where(short, int(self.params.short_overhead_tokens),
+                                                                   int(self.params.overhead_tokens))
         csum = np.concatenate([[0], np.cumsum(cost)])
         return csum[self.slot_ptr[1:]] - csum[self.slot_ptr[:-1]]
 

@@ -133,7 +133,7 @@ __device__ __forceinline__ void trace_stamp(const DecodeArgs &a, int what, bool 
 {
     if (a.trace && who) a.trace[static_cast<size_t>(blockIdx.x) * kTraceStamps + what] = wall_clock64();
 }
-constexpr int kEarlyTok = 256;            // tokens of a slot's first item that the early start may request
+constexpr int kEarlyTok = 384;            // tokens of a slot's first item that the early start may request
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
 __device__ __forceinline__ size_t out_row(const DecodeArgs &a, int b, int h, int c)
@@ -310,7 +310,7 @@ __device__ __forceinline__ void merge_round_many(const DecodeArgs &a, PendingPar
     constexpr int IT = (NC4 + kThreads - 1) / kThreads;            // coordinates per thread
     constexpr int MB = IT > 1 ? kMergeBatch / 2 : kMergeBatch;     // 6 IT kPend MB registers hold the batches
     float2 ml[IT][kPend][MB], o01[IT][kPend][MB], o23[IT][kPend][MB];
-    auto fetch_batch = [&](int it, int p, int c0) {
+    auto fetch_batch = [&](int it, int p, int c0) __attribute__((always_inline)) {
         const int idx = threadIdx.x + it * kThreads, g = idx / D4, d = (idx % D4) * 4;
         const int nc = pend.src_count[p], p0 = pend.src_first[p], st = pend.src_stride[p];
 #pragma unroll

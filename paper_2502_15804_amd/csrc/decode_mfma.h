@@ -46,7 +46,11 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
 typedef __attribute__((ext_vector_type(2))) int i32x2_t;
 
 constexpr int kTok = 16;      // tokens per tile (the M of the score MFMA, the K of the PV MFMA)
-constexpr int kStages = 2;    // tiles per wave resident in LDS: one being consumed, the others in flight (3 measured no faster)
+// Tiles per wave resident in LDS: one being consumed, the other in flight; 64 KB per compute unit are on their way
+// at any time.  Three stages (96 KB) fit the LDS for up to 8 columns and were measured side by side on one GPU:
+// 0.3-0.4 us slower per launch on the workloads that keep HBM saturated (deeper queues, no more bandwidth) and
+// no faster on the one that does not.
+constexpr int ring_stages(int) { return 2; }
 constexpr float kBump = 8.f;  // log2 units a score may exceed the reference maximum before it is raised
 
 #define FAIRKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -114,8 +118,15 @@ struct ItemSlot {
     int32_t n;        // tokens to read; 0 for an item that does not belong to this problem
     int32_t valid;    // 0: such an item; it is skipped
     int32_t b, h, chunk, n_chunks, part;
-    int32_t pad[3];
+    int32_t owner;    // -1: the four waves share the item's tiles; else the wave that runs the whole item alone
+    int32_t pad[2];
 };
+// A whole pair of at most this many tokens is run by one wave alone: it streams all the pair's tiles through its
+// own ring and writes the output straight from its registers, with no fold across waves and no barrier.  Short
+// pairs shared by four waves leave most of the rings empty (a 32-token pair is two tiles: two waves have nothing
+// to fetch and the other two one tile each), so a slot of many short pairs had about one pair in flight at a time
+// and each cost a memory round trip; alone, four pairs stream side by side.
+constexpr int kSoloTokens = FAIRKV_SHORT_PAIR_TOKENS;
 static_assert(sizeof(ItemSlot) == 48, "item table entry");
 constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches 32); longer slot lists go in batches
 
@@ -132,12 +143,16 @@ constexpr int kTable = 32 * kWaves;   // items per table fill (each wave fetches
 //                      j/8, j/8 + 2, ..., i.e. column j of tokens t_0 .. t_7 (layout checked on the GPU).
 // TRACE: the measurement instantiation behind fairkv_decode_attn_trace; it writes wall-clock stamps of its phases
 // (see trace_stamp) and is otherwise the same code.
-template <int D, int G, bool DEEP, bool KV8, bool TRACE = false>
+// SOLO: the plan has short whole pairs (at most kSoloTokens tokens) and they are run by single waves.  Plans
+// without any run an instantiation without that code: its presence alone cost 0.3-0.4 us per launch on every
+// workload (measured side by side on one GPU), on a kernel of under 20 us.
+template <int D, int G, bool DEEP, bool KV8, bool SOLO, bool TRACE = false>
 __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeArgs a)
 {
     static_assert(D == 64 || D == 128, "head_dim");
     static_assert(G >= 1 && G <= 16, "query heads of a group fit the N dimension");
     constexpr int TOK = KV8 ? 2 * kTok : kTok;          // tokens per stage and per step
+    constexpr int kStages = ring_stages(G);
     constexpr int kEarly = kStages < 3 ? kStages : 3;   // tiles per wave the early start may request
     static_assert(kStages >= 2 && kStages <= 4 && kEarlyTok >= kEarly * kWaves * TOK && kEarlyTok < 512, "ring, early start");
     static_assert(sizeof(fairkv_item) == 32, "two 16-byte pieces per item");
@@ -230,16 +245,20 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
         for (int nb_ = 0; nb_ < NDB; ++nb_) v_rd[nb_] = TILEB + vrow * ROWB + ((nb_ ^ ((2 * vrow) % PPR)) * 16) + (l16 & 1) * 8;
     }
 
-    // tiles of an n-token item that fall to this wave: tiles wave, wave + kWaves, ...
-    auto tiles_of = [&](int n) {
+    // tiles of an n-token item that fall to this wave: tiles wave, wave + kWaves, ... of an item the waves share;
+    // all of them, or none, of an item that one wave runs alone
+    auto tiles_of = [&](int n, int owner) __attribute__((always_inline)) {
         const int n_tiles = (n + TOK - 1) / TOK;
+        if (SOLO && owner >= 0) return owner == wave ? n_tiles : 0;
         return n_tiles > wave ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     };
+    // first token of this wave's t-th tile of an item
+    auto tile_tok0 = [&](int t, int owner) __attribute__((always_inline)) { return (SOLO && owner >= 0 ? t : wave + t * kWaves) * TOK; };
 
     // Fetch of this wave's t-th tile of an item into one stage: always exactly LOADS loads.
     // Rows past the end of the item re-read its last row (finite data with weight 0).
-    auto fetch = [&](int64_t row, int n, int t, int stage) {
-        const int tok0 = (wave + t * kWaves) * TOK;
+    auto fetch = [&](int64_t row, int n, int t, int owner, int stage) __attribute__((always_inline)) {
+        const int tok0 = tile_tok0(t, owner);
         const int last = n - 1 - tok0;
         const char *kbase = static_cast<const char *>(a.k) + (row + tok0) * ROWB;
         const char *vbase = static_cast<const char *>(a.v) + (row + tok0) * ROWB;
@@ -265,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // Fetch of the G query rows of pair (b, h) into one of the wave's q buffers: exactly QL loads.
     // Column c = (new token c >> g_shift, head c & mask) of q [B][q_len][Hq][D]: the heads of one new
     // token are contiguous, the new tokens are Hq rows apart.
-    auto fetch_q = [&](int b, int h, int buf) {
+    auto fetch_q = [&](int b, int h, int buf) __attribute__((always_inline)) {
         const char *src = static_cast<const char *>(a.q) +
                           (static_cast<size_t>(b) * a.q_len * a.Hq + (h << a.g_shift)) * QROWB;
 #pragma unroll
@@ -279,7 +298,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
 
     // Fetch of this wave's 32 of the kTable items that start at `first`: one load.  Past the end of
     // the slot's list the last item is read again.
-    auto fetch_items = [&](int first) {
+    auto fetch_items = [&](int first) __attribute__((always_inline)) {
         const int rel = min(32 * wave + (lane >> 1), i_end - 1 - first);
         load16_to_lds(a.items + first, rel * 32 + (lane & 1) * 16, raw_lds);
     };
@@ -288,15 +307,16 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // later items; `ahead` tiles are fetched and not yet consumed.  The query block of an item is
     // requested right before the item's first tile, into the q buffer of that tile's stage, so it
     // has landed when the tile has; bit s of q_mask says that the tile now in stage s came with one.
-    int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0, f_n = 0, f_tiles = 0, f_b = 0, f_h = 0;
+    int f_item = 0, f_t = 0, f_stage = 0, c_stage = 0, ahead = 0, f_n = 0, f_tiles = 0, f_b = 0, f_h = 0, f_owner = -1;
     int64_t f_row = 0;
     uint32_t q_mask = 0;
-    auto fetch_next = [&]() {      // the cursor's tile, f_t < f_tiles
+    auto fetch_next = [&]() __attribute__((always_inline)) {      // the cursor's tile, f_t < f_tiles
         if (f_t == 0) {
-            fetch_q(f_b, f_h, f_stage);
+            // (scalar registers for the load's base address, wherever the compiler kept these wave-uniform values)
+            fetch_q(__builtin_amdgcn_readfirstlane(f_b), __builtin_amdgcn_readfirstlane(f_h), f_stage);
             q_mask |= 1u << f_stage;
         }
-        fetch(f_row, f_n, f_t, f_stage);
+        fetch(f_row, f_n, f_t, f_owner, f_stage);
         f_stage = f_stage + 1 == kStages ? 0 : f_stage + 1;
         ++f_t;
         ++ahead;
@@ -311,11 +331,11 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     const bool seeded = n0 > 0;
     if (seeded) {
         const int pair0 = static_cast<int>(np0 >> 9);
-        f_b = pair0 / a.Hkv;
+        f_b = __builtin_amdgcn_readfirstlane(pair0 / a.Hkv);      // the division runs on the vector ALU
         f_h = pair0 - f_b * a.Hkv;
         f_row = a.first_row[blockIdx.x];
         f_n = n0;
-        f_tiles = tiles_of(n0);
+        f_tiles = tiles_of(n0, -1);          // the early start always shares the first item among the waves
         while (ahead < kEarly && f_t < f_tiles) fetch_next();
     }
 
@@ -337,14 +357,16 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             int n = ok ? max(it.tok_count, 0) : 0;      // a foreign item reads nothing
             if (early && threadIdx.x == 0)              // its first tiles are on their way, as many as n0 said
                 n = n0 < kEarlyTok ? n0 : max(n, kEarlyTok);
+            // short whole pairs go to single waves in turn (not the item the early start has already shared out)
+            const bool solo = SOLO && ok && it.n_chunks == 1 && n <= kSoloTokens && !(early && threadIdx.x == 0);
             table[threadIdx.x] = ItemSlot{it.row, n, ok ? 1 : 0, ok ? it.b : 0, ok ? it.h : 0,
-                                          it.chunk, it.n_chunks, it.part, {0, 0, 0}};
+                                          it.chunk, it.n_chunks, it.part, solo ? static_cast<int32_t>(threadIdx.x % kWaves) : -1, {0, 0}};
         }
         __syncthreads();
         if constexpr (TRACE)
             if (batch == i_begin) trace_stamp(a, kTraceTable, threadIdx.x == 0);
 
-        auto seek = [&](int item) {           // point the fetch cursor at an item of the table
+        auto seek = [&](int item) __attribute__((always_inline)) {           // point the fetch cursor at an item of the table
             f_item = item;
             f_t = 0;
             if (item < nb) {
@@ -352,18 +374,20 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
                 f_n = __builtin_amdgcn_readfirstlane(table[item].n);
                 f_b = __builtin_amdgcn_readfirstlane(table[item].b);
                 f_h = __builtin_amdgcn_readfirstlane(table[item].h);
+                f_owner = SOLO ? __builtin_amdgcn_readfirstlane(table[item].owner) : -1;
             } else {
                 f_n = 0;
+                f_owner = -1;
             }
-            f_tiles = tiles_of(f_n);
+            f_tiles = tiles_of(f_n, f_owner);
         };
         if (early) {                          // the cursor is already inside item 0: learn its full length
             f_n = __builtin_amdgcn_readfirstlane(table[0].n);
-            f_tiles = tiles_of(f_n);
+            f_tiles = tiles_of(f_n, -1);
         } else {
             seek(0);
         }
-        auto top_up = [&]() {
+        auto top_up = [&]() __attribute__((always_inline)) {
             while (ahead < kStages && f_item < nb) {
                 if (f_t < f_tiles)
                     fetch_next();
@@ -383,7 +407,9 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             it.n_chunks = __builtin_amdgcn_readfirstlane(table[ci].n_chunks);
             it.part = __builtin_amdgcn_readfirstlane(table[ci].part);
             const int n = __builtin_amdgcn_readfirstlane(table[ci].n);
-            const int my_tiles = tiles_of(n);
+            const int owner = SOLO ? __builtin_amdgcn_readfirstlane(table[ci].owner) : -1;
+            if (SOLO && owner >= 0 && owner != wave) continue;      // another wave runs this pair alone
+            const int my_tiles = tiles_of(n, owner);
             // scores to log2 units, and what multiplies the output: the same for every pair unless an 8-bit cache has
             // a scale per KV head
             const float s_mul = KV8 ? head_mul[it.h % kScaleHeads] : a.scale_log2;
@@ -438,7 +464,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
 #pragma unroll
                         for (int s = 0; s < NSL; ++s)
                             sacc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(kw[u * NSL + s]), qb[s], sacc[u], 0, 0, 0);
-                    const int tok0 = (wave + t * kWaves) * TOK;
+                    const int tok0 = tile_tok0(t, owner);
                     const bool masked = n - hidden_max - tok0 < TOK;     // some column does not see the whole step
                     float sv[8];
 #pragma unroll
@@ -499,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     #pragma unroll
                     for (int s = 0; s < NSL; ++s)
                         sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kw[s]), qb[s], sacc, 0, 0, 0);
-                    const int tok0 = (wave + t * kWaves) * TOK;
+                    const int tok0 = tile_tok0(t, owner);
                     const bool masked = n - hidden_max - tok0 < TOK;    // some column does not see the whole tile
                     float sv[4];
     #pragma unroll
@@ -555,6 +581,21 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             // ---- fold the four token quarters of l, stage this wave's result, finish the item ------
             l_run += __shfl_xor(l_run, 16, 64);
             l_run += __shfl_xor(l_run, 32, 64);
+            if (SOLO && owner >= 0) {
+                // This wave has seen the whole pair: out = O / l and lse straight from its registers.  A lane holds
+                // coordinates 16 nb + 4 lq .. + 3 of head l16.
+                if (l16 < G && __builtin_amdgcn_readfirstlane(table[ci].valid)) {
+                    const size_t orow = out_row(a, it.b, it.h, l16);
+                    const float inv = l_run > 0.f ? v_mul / l_run : 0.f;
+#pragma unroll
+                    for (int nb_ = 0; nb_ < NDB; ++nb_)
+                        store_out4(a.out, a.out_dtype, orow * D + 16 * nb_ + 4 * lq,
+                                   make_float4(o[nb_][0] * inv, o[nb_][1] * inv, o[nb_][2] * inv, o[nb_][3] * inv));
+                    if (lq == 0 && a.lse)
+                        a.lse[orow] = l_run > 0.f ? (m_run + __builtin_amdgcn_logf(l_run)) * kLn2 : -INFINITY;
+                }
+                continue;
+            }
             if (l16 < G) {
 #pragma unroll
                 for (int nb_ = 0; nb_ < NDB; ++nb_)

@@ -39,31 +39,43 @@ hipError_t launch_valu(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
     return hipGetLastError();
 }
 
-// The measurement instantiation exists for the shapes the benchmark traces: D = 128, bf16, plans without deeply cut pairs.
-hipError_t launch_mfma_trace(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
+// The measurement instantiation exists for the shapes the benchmark traces: D = 128, bf16, 4 or 8 query heads per KV head.
+hipError_t launch_mfma_trace(int G, bool deep, const DecodeArgs &a, int n_slots, hipStream_t st)
+{
+    const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
+    if (G == 4 && !deep)
+        hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 4, false, false, true, true>), grid, block, 0, st, a);
+    else if (G == 4)
+        hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 4, true, false, true, true>), grid, block, 0, st, a);
+    else if (G == 8 && !deep)
+        hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 8, false, false, true, true>), grid, block, 0, st, a);
+    else if (G == 8)
+        hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 8, true, false, true, true>), grid, block, 0, st, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+template <int D, bool DEEP, bool KV8, bool SOLO>
+hipError_t launch_mfma_g(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
 {
     const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
     switch (G) {
-    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 4, false, false, true>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<128, 8, false, false, true>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1, DEEP, KV8, SOLO>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2, DEEP, KV8, SOLO>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4, DEEP, KV8, SOLO>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8, DEEP, KV8, SOLO>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16, DEEP, KV8, SOLO>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
+// solo: the plan has short whole pairs behind the first item of a slot (the kernel gives those to single waves)
 template <int D, bool DEEP, bool KV8>
-hipError_t launch_mfma(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
+hipError_t launch_mfma(int G, bool solo, const DecodeArgs &a, int n_slots, hipStream_t st)
 {
-    const dim3 grid(static_cast<unsigned>(n_slots)), block(kThreads);
-    switch (G) {
-    case 1: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 1, DEEP, KV8>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 2, DEEP, KV8>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 4, DEEP, KV8>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 8, DEEP, KV8>), grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL((fairkv_decode_mfma_kernel<D, 16, DEEP, KV8>), grid, block, 0, st, a); break;
-    default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    return solo ? launch_mfma_g<D, DEEP, KV8, true>(G, a, n_slots, st) : launch_mfma_g<D, DEEP, KV8, false>(G, a, n_slots, st);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -294,9 +306,11 @@ int decode_common(const DecodeCall &c)
         for (int32_t i = 0; i < n_parts; ++i) count[i] = 0;
     }
     bool deep = false;      // a pair in very many pieces: the kernel with the two-level merge
+    bool solo = false;      // short whole pairs: the kernel that gives them to single waves
     for (int32_t i = 0; i < n_items; ++i) {
         const fairkv_item &it = items_host[i];
         deep |= it.n_chunks >= kDeepFrom;
+        solo |= it.n_chunks == 1 && it.tok_count <= kSoloTokens;
         if (it.b < 0 || it.b >= B || it.h < 0 || it.h >= Hkv || it.row < 0 || it.tok_count < 0) return FAIRKV_EINVAL;
         if (it.row + it.tok_count > c.n_rows) return FAIRKV_EINVAL;      // the kernel reads exactly these rows of K and V
         if (it.n_chunks < 1 || it.chunk < 0 || it.chunk >= it.n_chunks) return FAIRKV_EINVAL;
@@ -325,7 +339,6 @@ int decode_common(const DecodeCall &c)
     if (cols != 1 && cols != 2 && cols != 4 && cols != 8 && cols != 16) return FAIRKV_EUNSUPPORTED;
     if (q_len > 1 && (in_dtype != FAIRKV_BF16 || on_valu)) return FAIRKV_EUNSUPPORTED;
     if ((c.kv8 || c.trace) && on_valu) return FAIRKV_EUNSUPPORTED;
-    if (c.trace && deep) return FAIRKV_EUNSUPPORTED;
     if (!aligned16(c.k) || !aligned16(c.v) || !aligned16(c.q) || !aligned16(c.items) || !aligned16(c.out)) return FAIRKV_EINVAL;
     if (static_cast<int64_t>(B) * q_len * Hq * D > INT32_MAX) return FAIRKV_EINVAL;
     const size_t need = fairkv_workspace_bytes(n_parts, B * Hkv, static_cast<int32_t>(cols), D);
@@ -382,16 +395,16 @@ int decode_common(const DecodeCall &c)
     const bool kv8 = c.kv8;
     hipError_t e;
     if (c.trace)
-        e = launch_mfma_trace(static_cast<int>(cols), a, n_wg, st);
+        e = launch_mfma_trace(static_cast<int>(cols), deep, a, n_wg, st);
     else if (in_dtype == FAIRKV_BF16 && !on_valu)
-        e = kv8 ? (D == 128 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), a, n_wg, st)
-                                    : launch_mfma<128, false, true>(static_cast<int>(cols), a, n_wg, st))
-                            : (deep ? launch_mfma<64, true, true>(static_cast<int>(cols), a, n_wg, st)
-                                    : launch_mfma<64, false, true>(static_cast<int>(cols), a, n_wg, st)))
-            : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), a, n_wg, st)
-                               : launch_mfma<128, false, false>(static_cast<int>(cols), a, n_wg, st))
-                       : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), a, n_wg, st)
-                               : launch_mfma<64, false, false>(static_cast<int>(cols), a, n_wg, st));
+        e = kv8 ? (D == 128 ? (deep ? launch_mfma<128, true, true>(static_cast<int>(cols), solo, a, n_wg, st)
+                                    : launch_mfma<128, false, true>(static_cast<int>(cols), solo, a, n_wg, st))
+                            : (deep ? launch_mfma<64, true, true>(static_cast<int>(cols), solo, a, n_wg, st)
+                                    : launch_mfma<64, false, true>(static_cast<int>(cols), solo, a, n_wg, st)))
+            : D == 128 ? (deep ? launch_mfma<128, true, false>(static_cast<int>(cols), solo, a, n_wg, st)
+                               : launch_mfma<128, false, false>(static_cast<int>(cols), solo, a, n_wg, st))
+                       : (deep ? launch_mfma<64, true, false>(static_cast<int>(cols), solo, a, n_wg, st)
+                               : launch_mfma<64, false, false>(static_cast<int>(cols), solo, a, n_wg, st));
     else if (in_dtype == FAIRKV_BF16)
         e = D == 128 ? launch_valu<FAIRKV_BF16, 128>(G, a, n_wg, st) : launch_valu<FAIRKV_BF16, 64>(G, a, n_wg, st);
     else

@@ -27,7 +27,7 @@ bool params_ok(const fairkv_plan_params &p)
 {
     if (p.n_slots < 1 || p.tile < 1 || p.max_split < 1 || p.oversub < 1) return false;
     if (p.min_chunk < p.tile || p.min_chunk % p.tile != 0) return false;
-    if (p.overhead_tokens < 0 || p.reserved != 0) return false;
+    if (p.overhead_tokens < 0 || p.short_overhead_tokens < 0) return false;
     return p.policy >= FAIRKV_POLICY_NAIVE && p.policy <= FAIRKV_POLICY_FAIR;
 }
 
@@ -36,22 +36,33 @@ struct Piece {
     int32_t pair, begin, count, chunk, slot;
 };
 
+// Fixed cost of an item of `count` tokens: a whole pair of at most FAIRKV_SHORT_PAIR_TOKENS tokens is cheaper
+// for the kernel (one wave runs it alone), if the parameters say by how much.
+inline int64_t item_overhead(const fairkv_plan_params &p, int64_t count, bool whole_pair)
+{
+    return whole_pair && count <= FAIRKV_SHORT_PAIR_TOKENS && p.short_overhead_tokens > 0 ? p.short_overhead_tokens
+                                                                                          : p.overhead_tokens;
+}
+
 // FAIR: lay the pairs end to end and cut the line into n_slots pieces of equal cost.
 void cut_line(const int32_t *len, int64_t n_pairs, int64_t total, const fairkv_plan_params &p,
               std::vector<Piece> &pieces, std::vector<int32_t> &n_chunks)
 {
-    const int64_t S = p.n_slots, ov = p.overhead_tokens, tile = p.tile;
-    int64_t tokens_left = total, pairs_left = n_pairs;
+    const int64_t S = p.n_slots, tile = p.tile;
+    int64_t tokens_left = total;
+    int64_t ov_left = 0;      // fixed costs of the pairs not yet finished, each taken as one whole item
+    for (int64_t pair = 0; pair < n_pairs; ++pair) ov_left += item_overhead(p, len[pair], true);
     int64_t slot = 0;
     auto open_budget = [&](int64_t j) {
         const int64_t open_slots = S - j;
-        return ceil_div(tokens_left + ov * (pairs_left + open_slots), open_slots);
+        return ceil_div(tokens_left + ov_left + p.overhead_tokens * open_slots, open_slots);
     };
     int64_t room = open_budget(0);
     for (int64_t pair = 0; pair < n_pairs; ++pair) {
         int64_t left = len[pair], begin = 0;
         int32_t copies = 0;
         if (left == 0) {   // an empty pair still needs someone to write its zero output
+            const int64_t ov = item_overhead(p, 0, true);
             if (room < ov && slot < S - 1) room = open_budget(++slot);
             pieces.push_back({static_cast<int32_t>(pair), 0, 0, 0, static_cast<int32_t>(slot)});
             room -= ov;
@@ -59,9 +70,13 @@ void cut_line(const int32_t *len, int64_t n_pairs, int64_t total, const fairkv_p
         }
         while (left > 0) {
             const bool must_finish = slot == S - 1 || copies == p.max_split - 1;
+            // ov_take_all: the fixed cost if this item takes all that is left of the pair (a short pair taken whole
+            // has its own); a piece of a cut pair costs the full overhead.  fit: whole tiles that still fit.
+            const int64_t ov_take_all = item_overhead(p, left, begin == 0), ov = p.overhead_tokens;
+            const int64_t fit_all = std::max<int64_t>(0, (room - ov_take_all) / tile * tile);
             const int64_t fit = std::max<int64_t>(0, (room - ov) / tile * tile);
             int64_t take;
-            if (must_finish || left <= fit)
+            if (must_finish || left <= fit_all)
                 take = left;
             else if (fit >= p.min_chunk && left - fit >= p.min_chunk)
                 take = fit;
@@ -73,7 +88,7 @@ void cut_line(const int32_t *len, int64_t n_pairs, int64_t total, const fairkv_p
             }
             pieces.push_back({static_cast<int32_t>(pair), static_cast<int32_t>(begin), static_cast<int32_t>(take),
                               copies, static_cast<int32_t>(slot)});
-            room -= take + ov;
+            room -= take + (take == left ? ov_take_all : ov);
             begin += take;
             left -= take;
             tokens_left -= take;
@@ -81,7 +96,7 @@ void cut_line(const int32_t *len, int64_t n_pairs, int64_t total, const fairkv_p
             if (left > 0 && slot < S - 1) room = open_budget(++slot);
         }
         n_chunks[static_cast<size_t>(pair)] = copies;
-        --pairs_left;
+        ov_left -= item_overhead(p, len[pair], true);
     }
 }
 
@@ -97,7 +112,7 @@ extern "C" int fairkv_default_params(fairkv_plan_params *p, int32_t n_compute_un
     p->oversub = 2;
     p->overhead_tokens = 128;
     p->policy = FAIRKV_POLICY_FAIR;
-    p->reserved = 0;
+    p->short_overhead_tokens = 48;
     return FAIRKV_OK;
 }
 
@@ -165,7 +180,7 @@ extern "C" int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, in
                 Entry e = heap.top();
                 heap.pop();
                 pc.slot = e.second;
-                e.first += static_cast<int64_t>(pc.count) + p->overhead_tokens;
+                e.first += static_cast<int64_t>(pc.count) + item_overhead(*p, pc.count, n_chunks[static_cast<size_t>(pc.pair)] == 1);
                 heap.push(e);
             }
         }
@@ -183,7 +198,7 @@ extern "C" int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, in
     std::vector<int64_t> load(static_cast<size_t>(S), 0);
     for (const Piece &pc : pieces) {
         start[static_cast<size_t>(pc.slot) + 1] += 1;
-        load[static_cast<size_t>(pc.slot)] += static_cast<int64_t>(pc.count) + p->overhead_tokens;
+        load[static_cast<size_t>(pc.slot)] += static_cast<int64_t>(pc.count) + item_overhead(*p, pc.count, n_chunks[static_cast<size_t>(pc.pair)] == 1);
     }
     for (int32_t j = 0; j < S; ++j) start[j + 1] += start[j];
 

@@ -15,6 +15,7 @@ struct ProbeArgs {
 
 __global__ __launch_bounds__(kThreads, 1) void fairkv_stream_probe_kernel(ProbeArgs a)
 {
+    constexpr int kStages = ring_stages(8);      // the ring of the decode kernel for up to 8 columns
     constexpr int LPT = 4;                 // wave-wide loads per 4 KB K (or V) tile
     constexpr int TILEB = LPT * 1024;
     constexpr int STAGEB = 2 * TILEB;

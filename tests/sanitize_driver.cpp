@@ -2,7 +2,7 @@
 // AddressSanitizer and UndefinedBehaviorSanitizer (CPU only; see test_host_sanitizers.py).
 //
 // Reads one case per line from stdin and prints one result line per case:
-//   plan  B Hkv n_slots tile min_chunk max_split oversub overhead policy cap_mode  len[B*Hkv] off[B*Hkv]
+//   plan  B Hkv n_slots tile min_chunk max_split oversub overhead policy short_overhead cap_mode  len[B*Hkv] off[B*Hkv]
 //         -> "plan rc n_items n_parts max min | row tok b h chunk n_chunks part ... | slot_ptr ... | part_base ..."
 //            cap_mode 0: sized exactly; 1: one record too few (must return the capacity error and write no item)
 //   place n B tp max_extra max_copies mode  W[n]
@@ -41,8 +41,8 @@ struct Lcg {
 bool read_plan_args(std::istringstream &in, int32_t &B, int32_t &Hkv, fairkv_plan_params &p, int &cap_mode,
                     std::vector<int32_t> &len, std::vector<int64_t> &off)
 {
-    in >> B >> Hkv >> p.n_slots >> p.tile >> p.min_chunk >> p.max_split >> p.oversub >> p.overhead_tokens >> p.policy >> cap_mode;
-    p.reserved = 0;
+    in >> B >> Hkv >> p.n_slots >> p.tile >> p.min_chunk >> p.max_split >> p.oversub >> p.overhead_tokens >> p.policy >>
+        p.short_overhead_tokens >> cap_mode;
     if (!in || B < 1 || Hkv < 1 || B * Hkv > (1 << 20)) return false;
     len.resize(static_cast<size_t>(B) * Hkv);
     off.resize(len.size());

@@ -40,8 +40,9 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(F.fairkv_plan_params) == 32
     assert ctypes.sizeof(F.fairkv_plan_summary) == 32
     p = F.fairkv_default_params(256)
-    assert (p.n_slots, p.tile, p.min_chunk, p.max_split, p.oversub, p.overhead_tokens, p.policy) == \
-        (256, 16, 32, 256, 2, 128, F.FAIRKV_POLICY_FAIR)
+    assert (p.n_slots, p.tile, p.min_chunk, p.max_split, p.oversub, p.overhead_tokens, p.policy, p.short_overhead_tokens) == \
+        (256, 16, 32, 256, 2, 128, F.FAIRKV_POLICY_FAIR, 48)
+    assert F.FAIRKV_SHORT_PAIR_TOKENS == OP.SHORT_PAIR_TOKENS == 96
     d = OP.Params()
     assert (d.n_slots, d.tile, d.min_chunk, d.max_split, d.oversub, d.overhead_tokens, d.policy) == \
         (256, 16, 32, 256, 2, 128, OP.POLICY_FAIR)
@@ -51,6 +52,7 @@ def _same_as_oracle(lens, B, Hkv, offs=None, **kw):
     lens = np.asarray(lens).reshape(B, Hkv)
     if offs is None:
         offs = W.packed_offsets(lens, gap_rows=1)[0]
+    kw.setdefault("short_overhead_tokens", int(F.fairkv_default_params(1).short_overhead_tokens))   # the library's default
     op = OP.Params(**kw)
     o_items, o_slot_ptr, o_part_base, o_sum = OP.plan(lens.reshape(-1), np.asarray(offs).reshape(-1), B, Hkv, op)
     p = F.fairkv_default_params(1, **kw)
@@ -78,6 +80,8 @@ def test_plan_is_bit_exact_on_random_cases():
     for _ in range(1200):
         B, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 9))
         lens = rng.integers(0, 5001, size=(B, Hkv)).astype(np.int32)
+        short = rng.random((B, Hkv)) < 0.3           # short pairs: at most 96 tokens, with a fixed cost of their own
+        lens[short] = rng.integers(1, 130, size=int(short.sum()))
         lens[rng.random((B, Hkv)) < 0.1] = 0
         if rng.random() < 0.2:
             lens = (lens // 512) * 512          # many exact ties
@@ -85,7 +89,7 @@ def test_plan_is_bit_exact_on_random_cases():
         _same_as_oracle(lens, B, Hkv, n_slots=int(rng.integers(1, 65)), tile=tile,
                         min_chunk=tile * int(rng.integers(1, 9)), max_split=int(rng.integers(1, 40)),
                         oversub=int(rng.integers(1, 5)), overhead_tokens=int(rng.integers(0, 200)),
-                        policy=int(rng.integers(0, 4)))
+                        short_overhead_tokens=int(rng.choice([0, 0, 16, 48, 150])), policy=int(rng.integers(0, 4)))
 
 
 def test_plan_sizing_call_and_capacity_error():
@@ -114,7 +118,7 @@ def test_plan_all_empty_pairs():
 
 
 @pytest.mark.parametrize("bad", [dict(n_slots=0), dict(tile=0), dict(min_chunk=100), dict(max_split=0),
-                                 dict(oversub=0), dict(overhead_tokens=-1), dict(policy=4), dict(reserved=1),
+                                 dict(oversub=0), dict(overhead_tokens=-1), dict(policy=4), dict(short_overhead_tokens=-1),
                                  dict(min_chunk=0)])
 def test_plan_rejects_bad_parameters(bad):
     p = F.fairkv_default_params(4, **bad)

@@ -48,6 +48,7 @@ def _random_case(rng):
     kw = dict(n_slots=int(rng.choice([1, 2, 3, 7, 16, 64, 256, 320])), tile=tile, min_chunk=tile * int(rng.integers(1, 5)),
               overhead_tokens=int(rng.choice([0, 16, 128, 256])), max_split=int(rng.choice([2, 8, 1 << 20, 1 << 20, 1 << 20])),
               policy=P.POLICY_FAIR)
+    kw["short_overhead_tokens"] = int(rng.choice([0, kw["overhead_tokens"] // 3]))     # short pairs may cost less
     offs = W.packed_offsets(lens.reshape(B, Hkv), gap_rows=int(rng.integers(0, 3)))[0].reshape(-1)
     return lens, offs, B, Hkv, kw
 
@@ -79,7 +80,7 @@ def _check_contract(lens, offs, B, Hkv, kw, items, slot_ptr, max_load, min_load)
     assert sorted(x.part for x in items) == list(range(len(items)))
     # a line cut: the pairs' pieces appear in (pair, chunk) order along the slots
     assert [(x.b * Hkv + x.h, x.chunk) for x in items] == sorted((x.b * Hkv + x.h, x.chunk) for x in items)
-    loads = P.slot_loads(items, slot_ptr, ov)
+    loads = P.slot_loads(items, slot_ptr, ov, kw.get("short_overhead_tokens", 0))
     assert max(loads) == max_load and min(loads) == min_load and len(loads) == S
     return loads
 
@@ -95,7 +96,7 @@ def test_fair_contract_on_random_cases(impl):
         tile, mc, ov, S = kw["tile"], kw["min_chunk"], kw["overhead_tokens"], kw["n_slots"]
         total = int(lens.sum())
         # eq. 4's lower bound: no plan can have a largest load below the mean cost per slot
-        assert mx >= -(-(total + ov * len(items)) // S)
+        assert mx >= -(-(total + min(ov, kw["short_overhead_tokens"] or ov) * len(items)) // S)
         if kw["max_split"] < (1 << 20):
             continue                     # a capped pair ends in one long piece: the balance bound is not claimed
         # The budget of a slot never exceeds ceil((tokens + overhead * (pairs + slots)) / slots) by more than the
@@ -151,7 +152,8 @@ def test_fair_against_the_brute_force_optimum_on_tiny_inputs(impl):
         lens = rng.integers(1, 9, size=n_pairs).astype(np.int32) * 16 + rng.integers(0, 16, size=n_pairs).astype(np.int32)
         ov = int(rng.choice([0, 8, 32]))
         offs = W.packed_offsets(lens.reshape(n_pairs, 1))[0].reshape(-1)
-        kw = dict(n_slots=S, tile=tile, min_chunk=mc, overhead_tokens=ov, max_split=1 << 20, policy=P.POLICY_FAIR)
+        kw = dict(n_slots=S, tile=tile, min_chunk=mc, overhead_tokens=ov, max_split=1 << 20, policy=P.POLICY_FAIR,
+                  short_overhead_tokens=0)
         items, slot_ptr, mx, _ = impl(lens, offs, n_pairs, 1, **kw)
         opt = _best_contiguous_cut([int(x) for x in lens], S, tile, ov)
         assert opt <= mx, "a line cut cannot beat the best line cut"
@@ -168,7 +170,8 @@ def test_fair_on_the_workloads(impl):
         for layer in (0, 1):
             lens = W.lens(name, layer=layer).reshape(-1)
             offs = W.packed_offsets(lens.reshape(w.B, w.Hkv))[0].reshape(-1)
-            kw = dict(n_slots=256, tile=16, min_chunk=32, overhead_tokens=128, max_split=256, policy=P.POLICY_FAIR)
+            kw = dict(n_slots=256, tile=16, min_chunk=32, overhead_tokens=128, max_split=256, policy=P.POLICY_FAIR,
+                      short_overhead_tokens=48)
             items, slot_ptr, mx, mn = impl(lens, offs, w.B, w.Hkv, **kw)
             loads = _check_contract(lens, offs, w.B, w.Hkv, kw, items, slot_ptr, mx, mn)
             share = -(-(int(lens.sum()) + 128 * (lens.size + 256)) // 256)

@@ -50,7 +50,7 @@ def _run(exe, lines):
 
 def _plan_line(cmd, B, Hkv, kw, cap_mode, lens, offs, tail=""):
     return (f"{cmd} {B} {Hkv} {kw['n_slots']} {kw['tile']} {kw['min_chunk']} {kw['max_split']} {kw['oversub']} "
-            f"{kw['overhead_tokens']} {kw['policy']} {int(cap_mode)} " + " ".join(str(int(x)) for x in lens) + " " +
+            f"{kw['overhead_tokens']} {kw['policy']} {kw['short_overhead_tokens']} {int(cap_mode)} " + " ".join(str(int(x)) for x in lens) + " " +
             " ".join(str(int(x)) for x in offs) + tail)
 
 
@@ -61,7 +61,8 @@ def _plan_cases(rng, n):
         tile = int(rng.choice([1, 16, 64]))
         kw = dict(n_slots=int(rng.choice([1, 2, 5, 64, 320])), tile=tile, min_chunk=tile * int(rng.integers(1, 5)),
                   max_split=int(rng.choice([1, 2, 8, 256])), oversub=int(rng.integers(1, 4)),
-                  overhead_tokens=int(rng.choice([0, 16, 128])), policy=int(rng.integers(0, 4)))
+                  overhead_tokens=int(rng.choice([0, 16, 128])), policy=int(rng.integers(0, 4)),
+                  short_overhead_tokens=int(rng.choice([0, 8, 48])))
         offs = W.packed_offsets(lens.reshape(B, Hkv), gap_rows=int(rng.integers(0, 3)))[0].reshape(-1)
         yield B, Hkv, kw, lens, offs
 
@@ -71,9 +72,9 @@ def test_planner_differential_cases_under_sanitizers(driver):
     cases = list(_plan_cases(rng, 300))
     lines = [_plan_line("plan", B, Hkv, kw, i % 5 == 4, lens, offs) for i, (B, Hkv, kw, lens, offs) in enumerate(cases)]
     # arguments the planner must refuse without touching anything
-    lines.append("plan 1 1 0 16 32 8 2 128 3 0 5 0")
-    lines.append("plan 1 2 4 16 24 8 2 128 3 0 5 7 0 5")
-    lines.append("plan 1 1 4 16 32 8 2 128 3 0 -5 0")
+    lines.append("plan 1 1 0 16 32 8 2 128 3 0 0 5 0")
+    lines.append("plan 1 2 4 16 24 8 2 128 3 0 0 5 7 0 5")
+    lines.append("plan 1 1 4 16 32 8 2 128 3 0 0 -5 0")
     out = _run(driver, lines)
     assert out[-3:] == ["plan -1", "plan -1", "plan -1"]
     for i, ((B, Hkv, kw, lens, offs), got) in enumerate(zip(cases, out)):

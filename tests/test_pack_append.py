@@ -23,7 +23,8 @@ def test_plan_grow_matches_the_oracle_and_keeps_the_plan_valid():
         plan = F.fairkv_plan(lens, off, B, Hkv, p)
         ref_items, *_ = OP.plan(lens, off, B, Hkv, OP.Params(n_slots=p.n_slots, tile=p.tile, min_chunk=p.min_chunk,
                                                             max_split=p.max_split, oversub=p.oversub,
-                                                            overhead_tokens=p.overhead_tokens, policy=p.policy))
+                                                            overhead_tokens=p.overhead_tokens, policy=p.policy,
+                                                            short_overhead_tokens=p.short_overhead_tokens))
         items, l_lib, l_ref = plan.items.copy(), lens.copy(), [int(x) for x in lens]
         for step in range(3):
             F.fairkv_plan_grow(items, B, Hkv, l_lib, cap)
