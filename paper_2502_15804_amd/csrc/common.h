@@ -127,6 +127,7 @@ enum {
     kTraceFlushMerged,       // merges (if any) computed and written
     kTraceFlushEnd,
     kTraceEnd,               // last instruction
+    kTraceMergeLoaded,       // the first batch of partials of the merges has landed (this stamp makes the merge wait for it)
     kTraceStamps = 16
 };
 __device__ __forceinline__ void trace_stamp(const DecodeArgs &a, int what, bool who)
@@ -215,7 +216,7 @@ constexpr int kGroup = 8;
 constexpr int kDeepFrom = 32;
 enum { kRoleNone = 0, kRoleFinal = 1, kRoleGroup = 2 };
 
-template <int D, int G, bool DEEP>
+template <int D, int G, bool DEEP, bool TRACE = false>
 __device__ __forceinline__ void merge_round_one(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
 {
     // A thread owns four consecutive coordinates of one column.  The first batch of loads of ALL
@@ -240,6 +241,10 @@ __device__ __forceinline__ void merge_round_one(const DecodeArgs &a, PendingPart
                     o23[p][j] = fetch_f32x2(a.part_o + pg * D + d + 2);
                 }
             }
+        }
+        if constexpr (TRACE) {      // measurement only: when the first batch of partials has landed
+            drain_vmem();
+            trace_stamp(a, kTraceMergeLoaded, threadIdx.x == 0);
         }
 #pragma unroll
         for (int p = 0; p < kPend; ++p) {
@@ -387,11 +392,11 @@ __device__ __forceinline__ void merge_round_many(const DecodeArgs &a, PendingPar
 // Up to 256 float4 coordinates (G * D <= 1024) a thread owns at most one: the plain loop, whose code is the
 // shorter (0.2 us per launch on the headline workload: this code runs cold, on the tail).  With more, all of
 // a thread's coordinates are fetched together.
-template <int D, int G, bool DEEP>
+template <int D, int G, bool DEEP, bool TRACE = false>
 __device__ __forceinline__ void merge_round(const DecodeArgs &a, PendingParts<D, G> &pend, int n_pend)
 {
     if constexpr (G * D / 4 <= kThreads)
-        merge_round_one<D, G, DEEP>(a, pend, n_pend);
+        merge_round_one<D, G, DEEP, TRACE>(a, pend, n_pend);
     else
         merge_round_many<D, G, DEEP>(a, pend, n_pend);
 }
@@ -452,7 +457,7 @@ __device__ __forceinline__ void flush_pending(const DecodeArgs &a, PendingParts<
         }
         __syncthreads();
         if constexpr (TRACE) trace_stamp(a, kTraceFlushCounted, threadIdx.x == 0);
-        merge_round<D, G, DEEP>(a, pend, n_pend);
+        merge_round<D, G, DEEP, TRACE>(a, pend, n_pend);
         if constexpr (TRACE) trace_stamp(a, kTraceFlushMerged, threadIdx.x == 0);
         bool any_group = false;
         if (DEEP)
