@@ -61,12 +61,16 @@ def parse():
     ap.add_argument("--phases", action="store_true",
                     help="instead of the benchmark: one traced launch per layer (fairkv_decode_attn_trace) after a "
                          "warm rotation; prints where the time of a launch goes, per phase, from the GPU's wall clock")
+    ap.add_argument("--plan-sweep", action="store_true",
+                    help="instead of the benchmark: microseconds per layer of the four full-size workloads with the "
+                         "planner's cost parameters (overhead_tokens, short_overhead_tokens, min_chunk) varied one at a "
+                         "time around the defaults: the measurements the defaults of fairkv_default_params rest on")
     ap.add_argument("--phases-raw", default=None, metavar="FILE.npz",
                     help="with --phases: also save the stamps of every workgroup and what its slot held")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run three plain device-to-device copies of this size and exit: a kernel of "
                          "known traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
-    for name in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens"):
+    for name in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens", "short_overhead_tokens"):
         ap.add_argument("--" + name.replace("_", "-"), type=int, default=None)
     return ap.parse_args()
 
@@ -667,6 +671,43 @@ def phases(a, overrides):
     return rec
 
 
+def plan_sweep(a):
+    """The planner's cost parameters varied one at a time around the defaults, on every full-size workload: an item
+    costs tok_count + overhead (Section 3.2's offset of the linear latency model, in token units), and what that
+    offset should be is a property of the kernel that only a measurement gives."""
+    import torch
+    import workloads as W
+    import paper_2502_15804_amd as F
+
+    d = F.fairkv_default_params(256)
+    base = {"overhead_tokens": int(d.overhead_tokens), "short_overhead_tokens": int(d.short_overhead_tokens),
+            "min_chunk": int(d.min_chunk)}
+    grid = {"overhead_tokens": (32, 64, 96, 128, 160, 192, 256), "short_overhead_tokens": (16, 32, 48, 64, 96, 128),
+            "min_chunk": (16, 32, 64, 128, 256)}
+    layers = {"llama70b": 32, "mistral24b": 8, "faircopy": 8, "stress": 40}
+    out = {"experiment": "planner cost parameters, one varied at a time around the defaults; microseconds per layer "
+                         "(best of 3 graph-replayed passes over the rotation)", "defaults": base, "us_per_layer": {}}
+    for name, nl in layers.items():
+        res = {}
+        for key, values in grid.items():
+            row = {}
+            for v in values:
+                ov = dict(base)
+                ov[key] = v
+                r = Rotation(name, nl, a.seed, 3, ov)
+                best = min(1e6 * timed(r, nl * 8, nl, True)[1] / (nl * 8) for _ in range(3))
+                loads = r.layers[0].plan.slot_loads()
+                row[str(v)] = {"us": round(best, 2), "items_layer0": r.layers[0].plan.n_items,
+                               "E_layer0": round(float(loads.mean() / loads.max()), 3)}
+                del r
+                torch.cuda.empty_cache()
+            print(f"plan-sweep {name} {key}: " + " ".join(f"{v}:{x['us']}" for v, x in row.items()), file=sys.stderr,
+                  flush=True)
+            res[key] = row
+        out["us_per_layer"][name] = res
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -699,10 +740,13 @@ def main():
     if a.pack:
         print(json.dumps(pack_bench(a.seed, n_slots=a.n_slots)))
         return
+    if a.plan_sweep:
+        print(json.dumps(plan_sweep(a)))
+        return
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers
-    overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens")
-                 if getattr(a, k) is not None}
+    overrides = {k: getattr(a, k) for k in ("n_slots", "tile", "min_chunk", "max_split", "oversub", "overhead_tokens",
+                                            "short_overhead_tokens") if getattr(a, k) is not None}
     if a.phases:
         print(json.dumps(phases(a, overrides)))
         return
