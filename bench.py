@@ -65,6 +65,9 @@ def parse():
                     help="instead of the benchmark: microseconds per layer of the four full-size workloads with the "
                          "planner's cost parameters (overhead_tokens, short_overhead_tokens, min_chunk) varied one at a "
                          "time around the defaults: the measurements the defaults of fairkv_default_params rest on")
+    ap.add_argument("--probe-shapes", action="store_true",
+                    help="instead of the benchmark: the do-nothing reader in other launch shapes (waves per workgroup, "
+                         "ring stages, tile size, workgroups per compute unit) over the buffers of llama70b and mistral24b")
     ap.add_argument("--phases-raw", default=None, metavar="FILE.npz",
                     help="with --phases: also save the stamps of every workgroup and what its slot held")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -408,18 +411,19 @@ def latency_model(seed=0):
     return rec
 
 
-def stream_probe(rot, gbs):
+def stream_probe(rot, gbs, shape=None, wg_per_cu=1):
     """The same K/V bytes of the same rotation through fairkv_stream_probe: a reader with the decode kernel's
-    data path and launch shape and nothing to do.  Its rate is the ceiling this path can reach for this size."""
+    data path and launch shape and nothing to do.  Its rate is the ceiling this path can reach for this size.
+    shape = (waves, stages, tile_kib) and wg_per_cu select another launch shape (fairkv_stream_probe_shape)."""
     import torch
     import paper_2502_15804_amd as F
 
-    sink = torch.zeros(rot.n_cu, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(rot.n_cu * wg_per_cu, dtype=torch.int32, device="cuda")
     n = len(rot.layers)
 
     def run_all():
         for l in rot.layers:
-            F.fairkv_stream_probe(l.k, l.v, rot.n_cu, sink)
+            F.fairkv_stream_probe(l.k, l.v, rot.n_cu * wg_per_cu, sink, shape=shape)
 
     run_all()
     torch.cuda.synchronize()
@@ -673,6 +677,32 @@ def phases(a, overrides):
     return rec
 
 
+def probe_shapes(a):
+    """What the data path reaches as a function of the launch shape: waves per workgroup, ring stages, tile size
+    and workgroups per compute unit, hence bytes in flight per compute unit, on the K/V buffers of two workloads."""
+    import torch
+
+    out = {"experiment": "fairkv_stream_probe_shape over the layer buffers of a rotation, HIP-graph replay; "
+                         "us per layer and GB/s of K+V bytes", "shapes": {}}
+    shapes = [(4, 2, 2, 1), (4, 4, 2, 1), (4, 2, 4, 1), (4, 3, 4, 1), (4, 4, 4, 1), (4, 2, 8, 1),
+              (8, 2, 2, 1), (8, 4, 2, 1), (8, 2, 4, 1), (16, 2, 2, 1),
+              (4, 2, 2, 2), (4, 4, 2, 2), (4, 2, 4, 2), (4, 2, 2, 4)]
+    shapes = [x for x in shapes if x[0] * x[1] * 2 * x[2] * x[3] <= 160]      # rings side by side in 160 KB of LDS
+    for name, nl in (("llama70b", 32), ("mistral24b", 8)):
+        rot = Rotation(name, nl, a.seed, 3, {})
+        res = {}
+        for waves, stages, kib, per_cu in shapes:
+            r = min((stream_probe(rot, 1.0, (waves, stages, kib), per_cu) for _ in range(3)), key=lambda x: x["us_per_layer"])
+            key = f"{waves} waves x {stages} stages x 2x{kib} KiB, {per_cu} wg/CU"
+            res[key] = {"KiB_in_flight_per_CU": waves * stages * 2 * kib * per_cu, "us_per_layer": r["us_per_layer"],
+                        "GBs": r["GBs"]}
+            print(f"probe-shapes {name} {key}: {r['us_per_layer']} us {r['GBs']} GB/s", file=sys.stderr, flush=True)
+        out["shapes"][name] = res
+        del rot
+        torch.cuda.empty_cache()
+    return out
+
+
 def plan_sweep(a):
     """The planner's cost parameters varied one at a time around the defaults, on every full-size workload: an item
     costs tok_count + overhead (Section 3.2's offset of the linear latency model, in token units), and what that
@@ -744,6 +774,9 @@ def main():
         return
     if a.plan_sweep:
         print(json.dumps(plan_sweep(a)))
+        return
+    if a.probe_shapes:
+        print(json.dumps(probe_shapes(a)))
         return
     w = W.WORKLOADS[a.workload]
     n_layers = a.layers or w.n_layers

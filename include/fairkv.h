@@ -395,6 +395,14 @@ int fairkv_decode_attn_trace(const void *q, const void *k, const void *v, int64_
 int fairkv_stream_probe(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups, void *sink,
                         void *hip_stream);
 
+/* The same reader in another launch shape, for sweeping what the data path can reach: `waves` waves per workgroup
+ * (4, 8 or 16), each with a ring of `stages` stages (2, 3 or 4) of tile_kib KiB of K plus tile_kib KiB of V (2, 4 or
+ * 8); fairkv_stream_probe is (4, 2, 4), the decode kernel's shape.  bytes_each is rounded down to a multiple of
+ * tile_kib * 1024 * n_workgroups.  FAIRKV_EUNSUPPORTED for other values or when the rings exceed the 160 KB of LDS
+ * of a compute unit.  More workgroups than compute units share a compute unit when their rings fit side by side. */
+int fairkv_stream_probe_shape(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups, int32_t waves,
+                              int32_t stages, int32_t tile_kib, void *sink, void *hip_stream);
+
 const char *fairkv_strerror(int code);
 int fairkv_version(void);
 

@@ -29,7 +29,8 @@ EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fa
            "fairkv_decode_attn",
            "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8", "fairkv_decode_attn_kv8_per_head",
            "fairkv_decode_attn_static", "fairkv_decode_attn_trace",
-           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_strerror", "fairkv_version")
+           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_stream_probe_shape",
+           "fairkv_strerror", "fairkv_version")
 
 
 class fairkv_item(ctypes.Structure):
@@ -115,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.fairkv_plan_grow.argtypes = [vp, i32, i32, i32, vp, vp]
         L.fairkv_stream_probe.restype = ctypes.c_int
         L.fairkv_stream_probe.argtypes = [vp, vp, ctypes.c_int64, i32, vp, vp]
+        L.fairkv_stream_probe_shape.restype = ctypes.c_int
+        L.fairkv_stream_probe_shape.argtypes = [vp, vp, ctypes.c_int64, i32, i32, i32, i32, vp, vp]
         L.fairkv_decode_attn_multi.restype = ctypes.c_int
         L.fairkv_decode_attn_multi.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp, i32, vp, i32, i32, vp,
                                                ctypes.c_size_t, vp, vp, i32, i32, i32, i32, i32, i32, i32,
@@ -439,8 +442,9 @@ def fairkv_plan_grow(items: np.ndarray, B: int, Hkv: int, lens: np.ndarray, cap:
         raise FairKVError(rc, "fairkv_plan_grow")
 
 
-def fairkv_stream_probe(k, v, n_workgroups, sink, stream=None):
-    """Enqueue the do-nothing reader over all of the device tensors k and v (see the header)."""
+def fairkv_stream_probe(k, v, n_workgroups, sink, stream=None, shape=None):
+    """Enqueue the do-nothing reader over all of the device tensors k and v (see the header).
+    shape: (waves, stages, tile_kib) for fairkv_stream_probe_shape; None = the decode kernel's shape."""
     import torch
 
     _check_dev(k=k, v=v, sink=sink)
@@ -449,7 +453,11 @@ def fairkv_stream_probe(k, v, n_workgroups, sink, stream=None):
     if stream is None:
         stream = torch.cuda.current_stream(k.device)
     nbytes = min(k.numel() * k.element_size(), v.numel() * v.element_size())
-    rc = lib().fairkv_stream_probe(_ptr(k), _ptr(v), nbytes, int(n_workgroups), _ptr(sink),
-                                   ctypes.c_void_p(stream.cuda_stream))
+    if shape is not None:
+        rc = lib().fairkv_stream_probe_shape(_ptr(k), _ptr(v), nbytes, int(n_workgroups), int(shape[0]), int(shape[1]),
+                                             int(shape[2]), _ptr(sink), ctypes.c_void_p(stream.cuda_stream))
+    else:
+        rc = lib().fairkv_stream_probe(_ptr(k), _ptr(v), nbytes, int(n_workgroups), _ptr(sink),
+                                       ctypes.c_void_p(stream.cuda_stream))
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_stream_probe")

@@ -471,13 +471,66 @@ extern "C" int fairkv_append(const void *k_new, const void *v_new, int32_t B, in
 }
 
 // ---- measurement aid ------------------------------------------------------------------------------
+namespace {
+
+template <int WAVES, int STAGES, int LPT>
+int launch_probe(const ProbeArgs &a, int n_workgroups, hipStream_t st)
+{
+    constexpr size_t lds = static_cast<size_t>(WAVES) * STAGES * 2 * LPT * 1024;
+    if constexpr (lds > 160 * 1024 || 3 * (2 * LPT + 1) >= 64) {
+        return FAIRKV_EUNSUPPORTED;
+    } else {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&fairkv_stream_probe_kernel<WAVES, STAGES, LPT>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (attr != hipSuccess) return FAIRKV_EHIP;
+        hipLaunchKernelGGL((fairkv_stream_probe_kernel<WAVES, STAGES, LPT>), dim3(n_workgroups), dim3(WAVES * 64), lds, st, a);
+        return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
+    }
+}
+
+template <int WAVES, int STAGES>
+int launch_probe_t(int tile_kib, const ProbeArgs &a, int n, hipStream_t st)
+{
+    switch (tile_kib) {
+    case 2: return launch_probe<WAVES, STAGES, 2>(a, n, st);
+    case 4: return launch_probe<WAVES, STAGES, 4>(a, n, st);
+    case 8: return launch_probe<WAVES, STAGES, 8>(a, n, st);
+    default: return FAIRKV_EUNSUPPORTED;
+    }
+}
+
+template <int WAVES>
+int launch_probe_s(int stages, int tile_kib, const ProbeArgs &a, int n, hipStream_t st)
+{
+    switch (stages) {
+    case 2: return launch_probe_t<WAVES, 2>(tile_kib, a, n, st);
+    case 3: return launch_probe_t<WAVES, 3>(tile_kib, a, n, st);
+    case 4: return launch_probe_t<WAVES, 4>(tile_kib, a, n, st);
+    default: return FAIRKV_EUNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+extern "C" int fairkv_stream_probe_shape(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups,
+                                         int32_t waves, int32_t stages, int32_t tile_kib, void *sink, void *hip_stream)
+{
+    if (!k || !v || !sink || n_workgroups < 1 || bytes_each < 0 || !aligned16(k) || !aligned16(v)) return FAIRKV_EINVAL;
+    if (tile_kib < 1 || tile_kib > 8) return FAIRKV_EUNSUPPORTED;
+    ProbeArgs a{static_cast<const char *>(k), static_cast<const char *>(v),
+                bytes_each / n_workgroups / (tile_kib * 1024) * (tile_kib * 1024), static_cast<uint32_t *>(sink)};
+    if (a.bytes_per_workgroup * 16 > static_cast<int64_t>(UINT32_MAX)) return FAIRKV_EINVAL;   // 32-bit lane offsets
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (waves) {
+    case 4: return launch_probe_s<4>(stages, tile_kib, a, n_workgroups, st);
+    case 8: return launch_probe_s<8>(stages, tile_kib, a, n_workgroups, st);
+    case 16: return launch_probe_s<16>(stages, tile_kib, a, n_workgroups, st);
+    default: return FAIRKV_EUNSUPPORTED;
+    }
+}
+
 extern "C" int fairkv_stream_probe(const void *k, const void *v, int64_t bytes_each, int32_t n_workgroups,
                                    void *sink, void *hip_stream)
 {
-    if (!k || !v || !sink || n_workgroups < 1 || bytes_each < 0 || !aligned16(k) || !aligned16(v)) return FAIRKV_EINVAL;
-    ProbeArgs a{static_cast<const char *>(k), static_cast<const char *>(v),
-                bytes_each / n_workgroups / 4096 * 4096, static_cast<uint32_t *>(sink)};
-    if (a.bytes_per_workgroup * kWaves > static_cast<int64_t>(UINT32_MAX)) return FAIRKV_EINVAL;   // 32-bit lane offsets
-    hipLaunchKernelGGL(fairkv_stream_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), a);
-    return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
+    return fairkv_stream_probe_shape(k, v, bytes_each, n_workgroups, kWaves, ring_stages(8), 4, sink, hip_stream);
 }

@@ -24,11 +24,13 @@ def make_case(B, Hq, Hkv, D, dtype, lens, seed, gap_rows=0):
     return w, off, q, k, v
 
 
-def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison=True, calls=1, **params):
+def run_hip(w, q, k, v, off, lens, policy=3, n_slots=256, out_dtype=None, poison=True, calls=1, bf16_on_valu=False,
+            **params):
     from paper_2502_15804_amd.runtime import DecodeLayer
     F = _F()
     p = F.fairkv_default_params(256, policy=policy, n_slots=n_slots, **params)
-    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype)
+    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p, out_dtype=out_dtype,
+                        bf16_on_valu=bf16_on_valu)
     for _ in range(calls):      # a second call finds the workspace as the first left it
         counters = F.fairkv_workspace_counter_bytes(lens.size)              # the first region of the workspace
         if poison:
@@ -99,6 +101,24 @@ def test_chunked_equals_unchunked_on_the_gpu():
     assert np.abs(o1 - o2).max() < 2e-3 and np.abs(l1 - l2).max() < 2e-3
     ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
     assert np.abs(o1 - ro).max() <= w.tol and np.abs(o2 - ro).max() <= w.tol
+
+
+@pytest.mark.parametrize("D,G", [(128, 8), (128, 4), (64, 2)])
+def test_bf16_cache_on_the_vector_alu_kernel(D, G):
+    # FAIRKV_BF16_VALU: the same bf16 buffers and plan through the kernel that fp16 / fp32 caches use.  It keeps
+    # the softmax weights in fp32, so it sits much closer to the oracle than the matrix-core kernel's bar, and the
+    # two kernels, which share only the hand-over, agree with each other to the rounding of the weights to bf16.
+    rng = np.random.default_rng(40 + G)
+    lens = rng.integers(0, 1500, size=(3, 2)).astype(np.int32)
+    lens[0, 1] = 1
+    w, off, q, k, v = make_case(3, 2 * G, 2, D, "bf16", lens, seed=9, gap_rows=1)
+    for policy, n_slots in ((0, 16), (3, 16), (3, 5)):
+        err, _ = check(w, q, k, v, off, lens, tol=2e-5, policy=policy, n_slots=n_slots, min_chunk=64, bf16_on_valu=True)
+    o1, l1, _ = run_hip(w, q, k, v, off, lens, n_slots=16, min_chunk=64, bf16_on_valu=True)
+    o2, l2, _ = run_hip(w, q, k, v, off, lens, n_slots=16, min_chunk=64)
+    assert np.abs(o1 - o2).max() < 4e-3
+    keep = ~np.isneginf(l1)
+    assert np.array_equal(keep, ~np.isneginf(l2)) and np.abs(l1[keep] - l2[keep]).max() < 4e-3
 
 
 def test_all_heads_empty():
