@@ -57,10 +57,18 @@ __global__ __launch_bounds__(256) void fairkv_pack_kernel(PackArgs a)
         // All indices of a round first, then all row loads, then the stores: nothing in a round waits
         // for an earlier load of the same round.  Rows past the end and rows with a bad index are
         // loaded from a clamped (valid) address and not stored.
+        // The indices of the next round are requested before the rows of this one, so a round costs one
+        // memory latency (the rows), not two (index, then rows).
+        int32_t t_next[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) t_next[u] = kt[min(u * kRowsPerPass + sub, n - 1)];
         for (int r0 = 0; r0 < n; r0 += kRowsPerPass * kUnroll) {
             int32_t t[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) t[u] = kt[min(r0 + u * kRowsPerPass + sub, n - 1)];
+            for (int u = 0; u < kUnroll; ++u) {
+                t[u] = t_next[u];
+                t_next[u] = kt[min(r0 + (kUnroll + u) * kRowsPerPass + sub, n - 1)];
+            }
             uint4 kk[kUnroll], vv[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
