@@ -312,3 +312,19 @@ def test_static_and_trace_entry_points_validate_before_any_launch():
     assert trace(Hq=2) == F.FAIRKV_EUNSUPPORTED
     assert trace(n_slots=321) == F.FAIRKV_EUNSUPPORTED
     assert trace() == F.FAIRKV_EWORKSPACE                        # everything else valid: the 16-byte workspace is too small
+
+
+def test_stream_probe_shape_refuses_what_it_does_not_have():
+    L = F.lib()
+    fake = ctypes.c_void_p(0x1000)
+
+    def probe(k=fake, waves=4, stages=2, kib=4, n_wg=256, nbytes=1 << 24):
+        return L.fairkv_stream_probe_shape(k, fake, nbytes, n_wg, waves, stages, kib, fake, None)
+
+    assert probe(k=None) == F.FAIRKV_EINVAL
+    assert probe(k=ctypes.c_void_p(0x1008)) == F.FAIRKV_EINVAL          # not 16-byte aligned
+    assert probe(n_wg=0) == F.FAIRKV_EINVAL
+    assert probe(nbytes=-1) == F.FAIRKV_EINVAL
+    for bad in (dict(waves=5), dict(waves=32), dict(stages=1), dict(stages=5), dict(kib=3), dict(kib=16), dict(kib=0),
+                dict(waves=16, stages=4, kib=8), dict(waves=8, stages=3, kib=8)):      # the last two: rings beyond 160 KB
+        assert probe(**bad) == F.FAIRKV_EUNSUPPORTED, bad

@@ -574,3 +574,25 @@ def test_kv8_with_a_scale_per_kv_head():
         DecodeLayer(torch.zeros((1, 9, 128), dtype=torch.bfloat16).cuda(), k9, k9, np.zeros((1, 9), np.int64),
                     np.zeros((1, 9), np.int32), 0.1, k_scale=[1.0] * 9, v_scale=[1.0] * 9).run()
     assert e.value.code == F.FAIRKV_EUNSUPPORTED
+
+
+def test_stream_probe_runs_in_every_shape_it_offers():
+    # the measurement aid: nothing to compare, but every instantiation must launch, stay inside the buffers
+    # (the sizes below leave a ragged rest that it must not touch) and finish
+    F = _F()
+    k = torch.zeros(3 * (1 << 20) + 4096 + 16, dtype=torch.uint8, device="cuda")
+    v = torch.zeros_like(k)
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    for waves in (4, 8, 16):
+        for stages in (2, 3, 4):
+            for kib in (2, 4, 8):
+                for n_wg in (7, 256, 1024):
+                    if waves * stages * 2 * kib > 160:
+                        with pytest.raises(F.FairKVError) as e:
+                            F.fairkv_stream_probe(k, v, n_wg, sink, shape=(waves, stages, kib))
+                        assert e.value.code == F.FAIRKV_EUNSUPPORTED
+                    else:
+                        F.fairkv_stream_probe(k, v, n_wg, sink, shape=(waves, stages, kib))
+    F.fairkv_stream_probe(k, v, 256, sink)
+    torch.cuda.synchronize()
+    assert int(sink.count_nonzero().item()) == 0
