@@ -147,15 +147,20 @@ class Rotation:
         return g
 
 
+MAX_GRAPH_LAUNCHES = 4096      # longest graph the timed region is captured as (replays of a rotation beyond that)
+
+
 def timed(rot, steps, warmup, use_graph):
     """Returns (seconds by host clock, seconds by HIP events, bytes moved) for exactly `steps` steps.
 
-    With use_graph the timed region consists of graph replays only, whatever `steps` is: whole rotations are
-    replays of a graph of one rotation, and a remainder (or a run shorter than one rotation) is a graph of
-    exactly that many launches.  Without it every step is enqueued from Python."""
+    With use_graph the timed region consists of graph replays only, whatever `steps` is: up to MAX_GRAPH_LAUNCHES
+    steps are one replay of one graph of exactly that many launches (the launches rotate over the layers); longer
+    runs replay a graph of one rotation and a graph of the remainder.  Without it every step is enqueued from Python."""
     import torch
     n = len(rot.layers)
     full, rest = divmod(steps, n)
+    if use_graph and steps <= MAX_GRAPH_LAUNCHES:
+        full, rest = 0, steps                  # one graph of exactly `steps` launches, rotating over the layers
     g_full = rot.capture(n) if (use_graph and full) else None
     g_rest = rot.capture(rest) if (use_graph and rest) else None
 
@@ -178,7 +183,7 @@ def timed(rot, steps, warmup, use_graph):
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    moved = full * sum(rot.bytes) + sum(rot.bytes[:rest])
+    moved = full * sum(rot.bytes) + sum(rot.bytes[i % n] for i in range(rest))
     return t1 - t0, e0.elapsed_time(e1) * 1e-3, moved
 
 
@@ -812,9 +817,11 @@ def main():
                    "D": w.D, "layers_rotated": n_layers, "rotation_GB": round(sum(rot.bytes) / 1e9, 3),
                    "policy": a.policy, "n_slots": int(rot.params.n_slots), "min_chunk": int(rot.params.min_chunk),
                    "oversub": int(rot.params.oversub), "graph_replay": not a.no_graph,
-                   "timed_region": (f"HIP graph replays only: {a.steps // n_layers} x a graph of {n_layers} launches"
-                                    + (f" + 1 x a graph of {a.steps % n_layers} launches" if a.steps % n_layers else ""))
-                   if not a.no_graph else f"{a.steps} launches enqueued from Python",
+                   "timed_region": (f"{a.steps} launches enqueued from Python" if a.no_graph else
+                                    f"one replay of one HIP graph of {a.steps} launches rotating over the layers"
+                                    if a.steps <= MAX_GRAPH_LAUNCHES else
+                                    f"HIP graph replays only: {a.steps // n_layers} x a graph of {n_layers} launches"
+                                    + (f" + 1 x a graph of {a.steps % n_layers} launches" if a.steps % n_layers else "")),
                    "kernel": "vector ALU (A/B run)" if valu else "matrix cores",
                    "items_layer0": plan0.n_items},
         "us_per_layer": round(1e3 * ms_step, 3), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
