@@ -159,6 +159,12 @@ int fairkv_plan(const int32_t *len, const int64_t *off, int32_t B, int32_t Hkv, 
 size_t fairkv_workspace_counter_bytes(int32_t n_pairs);
 size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D);
 
+/* Sets the counter bytes of a device workspace (the first fairkv_workspace_counter_bytes(n_pairs) bytes) to zero
+ * with a small kernel on hip_stream, without synchronising: for a fresh workspace, and for one that a launch which
+ * did not complete may have left with non-zero counters.  workspace: device, 16-byte aligned, at least that many
+ * bytes (FAIRKV_EWORKSPACE otherwise).  Order it on the stream before the next decode call. */
+int fairkv_workspace_reset(void *workspace, size_t workspace_bytes, int32_t n_pairs, void *hip_stream);
+
 /*
  * Decode attention for one layer: for every sequence b and query head hq (KV head
  * h = hq / G), out[b][hq] = softmax(scale * q[b][hq] . K_rows^T) V_rows over the

@@ -29,7 +29,7 @@ EXPORTS = ("fairkv_default_params", "fairkv_plan", "fairkv_workspace_bytes", "fa
            "fairkv_decode_attn",
            "fairkv_decode_attn_multi", "fairkv_decode_attn_kv8", "fairkv_decode_attn_kv8_per_head",
            "fairkv_decode_attn_static", "fairkv_decode_attn_trace",
-           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_stream_probe_shape",
+           "fairkv_place", "fairkv_pack", "fairkv_append", "fairkv_plan_grow", "fairkv_stream_probe", "fairkv_stream_probe_shape", "fairkv_workspace_reset",
            "fairkv_strerror", "fairkv_version")
 
 
@@ -116,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.fairkv_plan_grow.argtypes = [vp, i32, i32, i32, vp, vp]
         L.fairkv_stream_probe.restype = ctypes.c_int
         L.fairkv_stream_probe.argtypes = [vp, vp, ctypes.c_int64, i32, vp, vp]
+        L.fairkv_workspace_reset.restype = ctypes.c_int
+        L.fairkv_workspace_reset.argtypes = [vp, ctypes.c_size_t, i32, vp]
         L.fairkv_stream_probe_shape.restype = ctypes.c_int
         L.fairkv_stream_probe_shape.argtypes = [vp, vp, ctypes.c_int64, i32, i32, i32, i32, vp, vp]
         L.fairkv_decode_attn_multi.restype = ctypes.c_int
@@ -440,6 +442,19 @@ def fairkv_plan_grow(items: np.ndarray, B: int, Hkv: int, lens: np.ndarray, cap:
     rc = lib().fairkv_plan_grow(items.ctypes.data, items.size, int(B), int(Hkv), lens.ctypes.data, cap.ctypes.data)
     if rc != FAIRKV_OK:
         raise FairKVError(rc, "fairkv_plan_grow")
+
+
+def fairkv_workspace_reset(workspace, n_pairs, stream=None):
+    """Enqueue the kernel that zeroes the counter bytes of a device workspace (see the header)."""
+    import torch
+
+    _check_dev(workspace=workspace)
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device)
+    rc = lib().fairkv_workspace_reset(_ptr(workspace), workspace.numel() * workspace.element_size(), int(n_pairs),
+                                      ctypes.c_void_p(stream.cuda_stream))
+    if rc != FAIRKV_OK:
+        raise FairKVError(rc, "fairkv_workspace_reset")
 
 
 def fairkv_stream_probe(k, v, n_workgroups, sink, stream=None, shape=None):

@@ -9,6 +9,7 @@
 // Section 4.2); the workgroup that delivers the last partial result of a pair combines them.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdint>
@@ -104,6 +105,27 @@ extern "C" size_t fairkv_workspace_counter_bytes(int32_t n_pairs)
 {
     if (n_pairs < 1) return 0;
     return align256((2 * static_cast<size_t>(n_pairs) + FAIRKV_MAX_SLOTS) * sizeof(int32_t));
+}
+
+namespace {
+__global__ __launch_bounds__(256) void fairkv_zero_words_kernel(uint32_t *p, size_t n_words)
+{
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n_words; i += static_cast<size_t>(gridDim.x) * 256)
+        p[i] = 0u;
+}
+}  // namespace
+
+// A fill kernel, not a memset: a caller may record this call into a HIP graph, where memset nodes are best avoided.
+extern "C" int fairkv_workspace_reset(void *workspace, size_t workspace_bytes, int32_t n_pairs, void *hip_stream)
+{
+    const size_t need = fairkv_workspace_counter_bytes(n_pairs);
+    if (!workspace || need == 0 || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0) return FAIRKV_EINVAL;
+    if (workspace_bytes < need) return FAIRKV_EWORKSPACE;
+    const size_t n_words = need / sizeof(uint32_t);
+    const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n_words + 255) / 256, 1024));
+    hipLaunchKernelGGL(fairkv_zero_words_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<uint32_t *>(workspace), n_words);
+    return hipGetLastError() == hipSuccess ? FAIRKV_OK : FAIRKV_EHIP;
 }
 
 extern "C" size_t fairkv_workspace_bytes(int32_t n_parts, int32_t n_pairs, int32_t G, int32_t D)

@@ -328,3 +328,13 @@ def test_stream_probe_shape_refuses_what_it_does_not_have():
     for bad in (dict(waves=5), dict(waves=32), dict(stages=1), dict(stages=5), dict(kib=3), dict(kib=16), dict(kib=0),
                 dict(waves=16, stages=4, kib=8), dict(waves=8, stages=3, kib=8)):      # the last two: rings beyond 160 KB
         assert probe(**bad) == F.FAIRKV_EUNSUPPORTED, bad
+
+
+def test_workspace_reset_validates_before_any_launch():
+    L = F.lib()
+    fake = ctypes.c_void_p(0x1000)
+    need = F.fairkv_workspace_counter_bytes(128)
+    assert L.fairkv_workspace_reset(None, need, 128, None) == F.FAIRKV_EINVAL
+    assert L.fairkv_workspace_reset(ctypes.c_void_p(0x1004), need, 128, None) == F.FAIRKV_EINVAL
+    assert L.fairkv_workspace_reset(fake, need, 0, None) == F.FAIRKV_EINVAL
+    assert L.fairkv_workspace_reset(fake, need - 1, 128, None) == F.FAIRKV_EWORKSPACE

@@ -596,3 +596,29 @@ def test_stream_probe_runs_in_every_shape_it_offers():
     F.fairkv_stream_probe(k, v, 256, sink)
     torch.cuda.synchronize()
     assert int(sink.count_nonzero().item()) == 0
+
+
+def test_workspace_reset_recovers_a_workspace_with_stale_counters():
+    # what a launch that died mid-way leaves behind: counters that are not zero.  After fairkv_workspace_reset the
+    # next call is right again; the rest of the workspace may hold anything.
+    F = _F()
+    from paper_2502_15804_amd.runtime import DecodeLayer
+    rng = np.random.default_rng(77)
+    lens = rng.integers(100, 2500, size=(2, 4)).astype(np.int32)
+    w, off, q, k, v = make_case(2, 16, 4, 128, "bf16", lens, seed=3)
+    p = F.fairkv_default_params(256, n_slots=24, min_chunk=64)
+    layer = DecodeLayer(q.cuda(), k.cuda(), v.cuda(), off, lens, w.scale, params=p)
+    assert layer.plan.n_items > 8
+    layer.workspace.fill_(0x5A)
+    F.fairkv_workspace_reset(layer.workspace, lens.size)
+    layer.run()
+    torch.cuda.synchronize()
+    counters = F.fairkv_workspace_counter_bytes(lens.size)
+    assert int(layer.workspace[:counters].count_nonzero().item()) == 0
+    ro, rl = OA.attention(W.to_numpy_bits(q), W.to_numpy_bits(k), W.to_numpy_bits(v), off, lens, w.scale)
+    assert np.abs(layer.out.float().cpu().numpy() - ro).max() <= w.tol
+    assert np.abs(layer.lse.cpu().numpy() - rl).max() <= w.tol
+    small = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(F.FairKVError) as e:
+        F.fairkv_workspace_reset(small, lens.size)
+    assert e.value.code == F.FAIRKV_EWORKSPACE
