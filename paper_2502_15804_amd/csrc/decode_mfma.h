@@ -60,9 +60,13 @@ constexpr float kBump = 8.f;  // log2 units a score may exceed the reference max
 // Written as inline assembly so that the compiler does not track it: it would otherwise
 // drain ALL outstanding loads (s_waitcnt vmcnt(0)) before any LDS read, which defeats the
 // multi-stage ring.  The waits are placed by hand with wait_vmcnt below.
+// The load is non-temporal (nt): K and V rows, query rows and item records are read once per launch, and a
+// stream marked that way does not displace or wait on the L2's other contents.  Measured against the same
+// kernel without the hint: 8 % less time per launch on the 188 MB and 174 MB layers, 4 % on the 68 MB layer,
+// 14 % on a layer of whole pairs of equal length; the sc0 / sc1 bits on top of it change nothing.
 __device__ __forceinline__ void load16_to_lds(const void *base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
 // s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt is split
