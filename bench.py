@@ -578,6 +578,13 @@ def other_workloads(a, overrides):
             sys.exit(1)
         del r
         torch.cuda.empty_cache()
+        if a.policy == 3:      # the same kernel with one whole pair per workgroup: the balanced-against-naive gain here too
+            r0 = Rotation(name, n, a.seed, 0, overrides)
+            _, ev0, moved0 = timed(r0, steps, n, not a.no_graph)
+            out[name]["naive_GBs"] = round(moved0 / ev0 / 1e9, 1)
+            out[name]["gain_vs_naive"] = round(gbs / (moved0 / ev0 / 1e9), 3)
+            del r0
+            torch.cuda.empty_cache()
     return out
 
 
