@@ -60,13 +60,19 @@ constexpr float kBump = 8.f;  // log2 units a score may exceed the reference max
 // Written as inline assembly so that the compiler does not track it: it would otherwise
 // drain ALL outstanding loads (s_waitcnt vmcnt(0)) before any LDS read, which defeats the
 // multi-stage ring.  The waits are placed by hand with wait_vmcnt below.
-// The load is non-temporal (nt): K and V rows, query rows and item records are read once per launch, and a
-// stream marked that way does not displace or wait on the L2's other contents.  Measured against the same
-// kernel without the hint: 8 % less time per launch on the 188 MB and 174 MB layers, 4 % on the 68 MB layer,
+// The load is non-temporal (nt): K and V rows are read once per launch, and a stream marked that way does not
+// displace or wait on the L2's other contents.  Measured against the same kernel without the hint: 8 % less time per launch on the 188 MB and 174 MB layers, 4 % on the 68 MB layer,
 // 14 % on a layer of whole pairs of equal length; the sc0 / sc1 bits on top of it change nothing.
 __device__ __forceinline__ void load16_to_lds(const void *base, uint32_t off, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
+}
+// The same without the hint, for what several workgroups read (the query rows of a pair whose pieces sit in
+// different slots) or what comes back on every decode step (a layer's item list): 0.3 us per launch less on the
+// workloads with many cut pairs or many items, 0.2 us more on a layer of whole pairs.
+__device__ __forceinline__ void load16_to_lds_keep(const void *base, uint32_t off, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
 // s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt is split
@@ -301,7 +307,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
             const int o = min(i * 1024 + lane * 16, QBYTES - 16);      // byte o of the [G][QROWB] image in LDS
             const int c = o / QROWB;
             const int row = (c >> a.g_shift) * a.Hq + (c & ((1 << a.g_shift) - 1));
-            load16_to_lds(src, row * QROWB + o % QROWB, q_lds + buf * QBUF + i * 1024);
+            load16_to_lds_keep(src, row * QROWB + o % QROWB, q_lds + buf * QBUF + i * 1024);
         }
     };
 
@@ -309,7 +315,7 @@ __global__ __launch_bounds__(kThreads, 1) void fairkv_decode_mfma_kernel(DecodeA
     // the slot's list the last item is read again.
     auto fetch_items = [&](int first) __attribute__((always_inline)) {
         const int rel = min(32 * wave + (lane >> 1), i_end - 1 - first);
-        load16_to_lds(a.items + first, rel * 32 + (lane & 1) * 16, raw_lds);
+        load16_to_lds_keep(a.items + first, rel * 32 + (lane & 1) * 16, raw_lds);
     };
 
     // Ring bookkeeping: the fetch cursor (f_*) runs ahead of the compute cursor, possibly into
