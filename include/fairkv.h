@@ -108,9 +108,9 @@ typedef struct {
 } fairkv_plan_summary;
 
 /* Defaults: n_slots = n_compute_units, tile 16, min_chunk 32, max_split 256, oversub 2,
- * overhead_tokens 128 (measured on MI355X: an extra item in a slot costs about as much as
- * streaming 100-150 tokens), short_overhead_tokens 48 (a short pair costs a slot about a third
- * of that), policy FAIR.  n_compute_units must be >= 1. */
+ * overhead_tokens 160 (measured on MI355X: an extra item in a slot costs about as much as
+ * streaming 120-160 tokens, and the time per launch is flat from 128 to 192), short_overhead_tokens 48
+ * (a short pair costs a slot about a third of that), policy FAIR.  n_compute_units must be >= 1. */
 int fairkv_default_params(fairkv_plan_params *p /*host, out*/, int32_t n_compute_units);
 
 /*

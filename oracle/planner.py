@@ -50,7 +50,7 @@ class Params:
     min_chunk: int = 32
     max_split: int = 256
     oversub: int = 2
-    overhead_tokens: int = 128
+    overhead_tokens: int = 160
     policy: int = POLICY_FAIR
     short_overhead_tokens: int = 0    # fixed cost of a short pair (a whole pair of at most SHORT_PAIR_TOKENS); 0: overhead_tokens
 

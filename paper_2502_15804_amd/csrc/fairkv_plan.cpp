@@ -110,7 +110,7 @@ extern "C" int fairkv_default_params(fairkv_plan_params *p, int32_t n_compute_un
     p->min_chunk = 32;
     p->max_split = 256;
     p->oversub = 2;
-    p->overhead_tokens = 128;
+    p->overhead_tokens = 160;
     p->policy = FAIRKV_POLICY_FAIR;
     p->short_overhead_tokens = 48;
     return FAIRKV_OK;

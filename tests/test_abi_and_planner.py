@@ -41,11 +41,11 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(F.fairkv_plan_summary) == 32
     p = F.fairkv_default_params(256)
     assert (p.n_slots, p.tile, p.min_chunk, p.max_split, p.oversub, p.overhead_tokens, p.policy, p.short_overhead_tokens) == \
-        (256, 16, 32, 256, 2, 128, F.FAIRKV_POLICY_FAIR, 48)
+        (256, 16, 32, 256, 2, 160, F.FAIRKV_POLICY_FAIR, 48)
     assert F.FAIRKV_SHORT_PAIR_TOKENS == OP.SHORT_PAIR_TOKENS == 96
     d = OP.Params()
     assert (d.n_slots, d.tile, d.min_chunk, d.max_split, d.oversub, d.overhead_tokens, d.policy) == \
-        (256, 16, 32, 256, 2, 128, OP.POLICY_FAIR)
+        (256, 16, 32, 256, 2, 160, OP.POLICY_FAIR)
 
 
 def _same_as_oracle(lens, B, Hkv, offs=None, **kw):
