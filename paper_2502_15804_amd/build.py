@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfairkv.so")
 SOURCES = [os.path.join(CSRC, "fairkv_api.hip"), os.path.join(CSRC, "fairkv_plan.cpp"),
            os.path.join(CSRC, "fairkv_place.cpp")]
-HEADERS = [os.path.join(ROOT, "include", "fairkv.h")] + [os.path.join(CSRC, h) for h in ("common.h", "decode_mfma.h", "decode_valu.h", "pack.h", "stream_probe.h")]
+HEADERS = [os.path.join(ROOT, "include", "fairkv.h"), os.path.join(ROOT, "include", "fairkv_measure.h")] + [os.path.join(CSRC, h) for h in ("common.h", "decode_mfma.h", "decode_valu.h", "pack.h", "stream_probe.h")]
 
 
 def is_stale() -> bool:

@@ -21,6 +21,7 @@
 #include "pack.h"
 #include "stream_probe.h"
 #include "fairkv.h"
+#include "fairkv_measure.h"
 
 namespace {
 

@@ -24,7 +24,8 @@ def _built():
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "fairkv.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                  if h.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(fairkv_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(F.EXPORTS)
