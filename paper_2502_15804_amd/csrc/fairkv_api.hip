@@ -26,6 +26,7 @@
 namespace {
 
 using namespace fairkv;
+static_assert(kTraceStamps == FAIRKV_TRACE_STAMPS, "the header's stamp count is the kernel's");
 
 template <int IN_DT, int D>
 hipError_t launch_valu(int G, const DecodeArgs &a, int n_slots, hipStream_t st)
